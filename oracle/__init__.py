@@ -1,0 +1,12 @@
+"""CPU oracle for the paged KV-cache data path (test infrastructure only).
+
+Only the tests, the smoke check and the bench's CPU-baseline leg may import
+this package; the product package never does.
+"""
+from .kv_oracle import (  # noqa: F401
+    OracleError,
+    build,
+    decode_attn,
+    pack_blocks,
+    restore_blocks,
+)

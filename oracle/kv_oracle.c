@@ -1,0 +1,203 @@
+/*
+ * CPU oracle for the paged KV-cache data path.  TEST INFRASTRUCTURE ONLY: it is
+ * the slow, plain definition that the GPU library is checked against; nothing
+ * in the product path may call it.
+ *
+ * What it defines
+ *   - decode attention of one query token per sequence over that sequence's
+ *     cached keys/values, where the cache is stored as fixed-size blocks that a
+ *     per-sequence block table maps from logical to physical position.  This is
+ *     the "block representation of KV cache" that Sec. 3.2 item 3 (Background
+ *     KV Cache Replication) of the paper builds on; the attention formula is
+ *     the textbook scaled dot-product attention with grouped query heads
+ *     (consecutive query heads share one KV head).
+ *   - block-by-block replication (Sec. 3.2 item 3, Sec. 4.4): gather listed
+ *     pool blocks into a contiguous replica, and the inverse used when a
+ *     replication target continues requests "from the replicated state".
+ *
+ * All floating point is IEEE double.  Inputs are bf16 bit patterns (uint16)
+ * widened exactly: bf16 -> fp32 by a 16-bit left shift -> double.
+ *
+ * Pool layout: [num_blocks][2][num_kv_heads][block_size][head_dim] bf16,
+ * index 0 of the second axis is K, index 1 is V.  Only the accessor kv_at()
+ * knows this.
+ *
+ * No blocking, fusion or reordering: scores in ascending token order, then the
+ * max, then the weights, then their sum, then the weighted sum of V rows.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+    const uint16_t* base;
+    int64_t num_blocks;
+    int num_kv_heads, block_size, head_dim;
+} pool_view;
+
+static double bf16_to_double(uint16_t bits)
+{
+    uint32_t w = ((uint32_t)bits) << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+/* which: 0 = key, 1 = value; p physical block; kvh KV head; r row in block; d channel */
+static double kv_at(const pool_view* pv, int which, int64_t p, int kvh, int r, int d)
+{
+    int64_t idx = (((p * 2 + which) * pv->num_kv_heads + kvh) * pv->block_size + r) * (int64_t)pv->head_dim + d;
+    return bf16_to_double(pv->base[idx]);
+}
+
+/* One (sequence, query head) output row.  s and w are caller scratch of >= L doubles. */
+static void decode_row(double* out_row, const uint16_t* q_row, const pool_view* pv,
+                       const int32_t* table_row, int L, int kvh, double scale,
+                       double* s, double* w)
+{
+    const int D = pv->head_dim, bs = pv->block_size;
+    if (L == 0) {
+        for (int d = 0; d < D; ++d) out_row[d] = 0.0;
+        return;
+    }
+    for (int t = 0; t < L; ++t) {
+        int64_t p = table_row[t / bs];
+        int r = t % bs;
+        double dot = 0.0;
+        for (int d = 0; d < D; ++d) dot += bf16_to_double(q_row[d]) * kv_at(pv, 0, p, kvh, r, d);
+        s[t] = scale * dot;
+    }
+    double m = s[0];
+    for (int t = 1; t < L; ++t) if (s[t] > m) m = s[t];
+    double l = 0.0;
+    for (int t = 0; t < L; ++t) { w[t] = exp(s[t] - m); l += w[t]; }
+    for (int d = 0; d < D; ++d) {
+        double acc = 0.0;
+        for (int t = 0; t < L; ++t) {
+            int64_t p = table_row[t / bs];
+            acc += w[t] * kv_at(pv, 1, p, kvh, t % bs, d);
+        }
+        out_row[d] = acc / l;
+    }
+}
+
+static int check_decode_args(int64_t num_blocks, int num_kv_heads, int block_size, int head_dim,
+                             const int32_t* block_table, int max_blocks_per_seq,
+                             const int32_t* context_lens, int batch, int num_q_heads)
+{
+    if (num_blocks <= 0 || num_kv_heads <= 0 || block_size <= 0 || head_dim <= 0) return -2;
+    if (batch < 0 || num_q_heads <= 0 || num_q_heads % num_kv_heads != 0) return -2;
+    for (int b = 0; b < batch; ++b) {
+        int L = context_lens[b];
+        if (L < 0 || (int64_t)L > (int64_t)max_blocks_per_seq * block_size) return -3;
+        int nb = (L + block_size - 1) / block_size;
+        for (int j = 0; j < nb; ++j) {
+            int32_t p = block_table[(int64_t)b * max_blocks_per_seq + j];
+            if (p < 0 || p >= num_blocks) return -4;
+        }
+    }
+    return 0;
+}
+
+/*
+ * rows: optional list of n_rows (b, h) pairs (int32[2*n_rows]); when NULL every
+ * (b, h) is computed and out is [batch][num_q_heads][head_dim]; otherwise out
+ * is [n_rows][head_dim].  Returns the number of threads used (>= 1) or a
+ * negative error.
+ */
+int kvo_decode_attn(double* out, const uint16_t* q, const uint16_t* pool, int64_t num_blocks,
+                    int num_kv_heads, int block_size, int head_dim,
+                    const int32_t* block_table, int max_blocks_per_seq,
+                    const int32_t* context_lens, int batch, int num_q_heads, float scale,
+                    const int32_t* rows, int64_t n_rows, int num_threads)
+{
+    int rc = check_decode_args(num_blocks, num_kv_heads, block_size, head_dim, block_table,
+                               max_blocks_per_seq, context_lens, batch, num_q_heads);
+    if (rc) return rc;
+    pool_view pv = { pool, num_blocks, num_kv_heads, block_size, head_dim };
+    const int G = num_q_heads / num_kv_heads;
+    const int64_t total = rows ? n_rows : (int64_t)batch * num_q_heads;
+    int maxL = 1;
+    for (int b = 0; b < batch; ++b) if (context_lens[b] > maxL) maxL = context_lens[b];
+    int used = 1;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+#pragma omp parallel
+#endif
+    {
+        double* s = (double*)malloc(sizeof(double) * (size_t)maxL);
+        double* w = (double*)malloc(sizeof(double) * (size_t)maxL);
+#ifdef _OPENMP
+#pragma omp single
+        used = omp_get_num_threads();
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t i = 0; i < total; ++i) {
+            int b = rows ? rows[2 * i] : (int)(i / num_q_heads);
+            int h = rows ? rows[2 * i + 1] : (int)(i % num_q_heads);
+            decode_row(out + i * head_dim, q + ((int64_t)b * num_q_heads + h) * head_dim, &pv,
+                       block_table + (int64_t)b * max_blocks_per_seq, context_lens[b], h / G,
+                       (double)scale, s, w);
+        }
+        free(s);
+        free(w);
+    }
+    return used;
+}
+
+/* replica[i] <- pool[ids[i]], whole blocks, list order; ids may repeat. */
+int kvo_pack_blocks(uint8_t* replica, const uint8_t* pool, int64_t block_bytes, int64_t num_blocks,
+                    const int32_t* ids, int64_t n, int num_threads)
+{
+    for (int64_t i = 0; i < n; ++i) if (ids[i] < 0 || ids[i] >= num_blocks) return -4;
+    int used = 1;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < n; ++i)
+            memcpy(replica + i * block_bytes, pool + (int64_t)ids[i] * block_bytes, (size_t)block_bytes);
+    }
+#else
+    for (int64_t i = 0; i < n; ++i)
+        memcpy(replica + i * block_bytes, pool + (int64_t)ids[i] * block_bytes, (size_t)block_bytes);
+#endif
+    return used;
+}
+
+/* pool[ids[i]] <- replica[i]; ids must be pairwise distinct (else -5, nothing written). */
+int kvo_restore_blocks(uint8_t* pool, const uint8_t* replica, int64_t block_bytes, int64_t num_blocks,
+                       const int32_t* ids, int64_t n, int num_threads)
+{
+    uint8_t* seen = (uint8_t*)calloc((size_t)num_blocks, 1);
+    if (!seen) return -6;
+    for (int64_t i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= num_blocks) { free(seen); return -4; }
+        if (seen[ids[i]]) { free(seen); return -5; }
+        seen[ids[i]] = 1;
+    }
+    free(seen);
+    int used = 1;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < n; ++i)
+            memcpy(pool + (int64_t)ids[i] * block_bytes, replica + i * block_bytes, (size_t)block_bytes);
+    }
+#else
+    for (int64_t i = 0; i < n; ++i)
+        memcpy(pool + (int64_t)ids[i] * block_bytes, replica + i * block_bytes, (size_t)block_bytes);
+#endif
+    return used;
+}

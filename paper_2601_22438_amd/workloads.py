@@ -1,0 +1,296 @@
+"""Seeded synthetic inputs for the paged KV-cache data path.
+
+This module only draws random inputs and lays them out; it holds none of the
+arithmetic of attention or of block replication, and it is the one module that
+both the GPU tests/bench and the CPU oracle's callers use.
+
+The paper (Sec. 4) drives its system with chat requests served by an 8B
+Llama-family model; neither is reproduced here.  The cases below stand in for
+the *shapes* of that workload: Llama-style grouped-query attention geometry,
+block-paged caches with shuffled block tables, and uniform or log-normal
+context-length mixes.  All values are bf16 draws of N(0, 1), kept as uint16 bit
+patterns in numpy arrays.
+
+Pool layout: [num_blocks][2][num_kv_heads][block_size][head_dim], axis 1 is
+(K, V).  Unused pool blocks and unused tail slots are filled with random data
+too, so that touching a wrong block shows up as a wrong result.
+"""
+from __future__ import annotations
+
+import math
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_CHUNK_ELEMS = 1 << 22          # elements drawn per child generator
+_GEN_THREADS = 8
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bf16 (nearest, ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns (uint16) to float32 exactly."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def normal_bf16(seed_seq: np.random.SeedSequence, shape) -> np.ndarray:
+    """bf16 bit patterns of N(0,1) draws, deterministic for (seed_seq, shape).
+
+    The flat array is cut into fixed-size chunks, each drawn from its own child
+    of ``seed_seq``, so the result does not depend on the number of threads.
+    """
+    n = int(np.prod(shape, dtype=np.int64))
+    out = np.empty(n, dtype=np.uint16)
+    n_chunks = max(1, -(-n // _CHUNK_ELEMS))
+    children = seed_seq.spawn(n_chunks)
+
+    def fill(i):
+        lo = i * _CHUNK_ELEMS
+        hi = min(n, lo + _CHUNK_ELEMS)
+        g = np.random.default_rng(children[i])
+        out[lo:hi] = f32_to_bf16_bits(g.standard_normal(hi - lo, dtype=np.float32))
+
+    if n_chunks == 1:
+        fill(0)
+    else:
+        with ThreadPoolExecutor(_GEN_THREADS) as ex:
+            list(ex.map(fill, range(n_chunks)))
+    return out.reshape(shape)
+
+
+@dataclass
+class Geometry:
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int
+    block_size: int
+
+    @property
+    def group(self) -> int:
+        return self.num_q_heads // self.num_kv_heads
+
+    @property
+    def block_elems(self) -> int:
+        return 2 * self.num_kv_heads * self.block_size * self.head_dim
+
+    @property
+    def block_bytes(self) -> int:
+        return 2 * self.block_elems
+
+    @property
+    def kv_bytes_per_token(self) -> int:
+        return 2 * self.num_kv_heads * self.head_dim * 2
+
+    @property
+    def scale(self) -> np.float32:
+        return np.float32(1.0 / math.sqrt(self.head_dim))
+
+
+@dataclass
+class DecodeCase:
+    """One batch of decode inputs over a block pool, plus a dirty-block list."""
+    name: str
+    geom: Geometry
+    context_lens: np.ndarray            # int32 [B]
+    block_table: np.ndarray             # int32 [B][MB], unused entries -1
+    num_blocks: int
+    q: np.ndarray                       # uint16 [B][Hq][D]
+    pool: np.ndarray | None             # uint16 [NB][2][Hkv][bs][D] (None if not materialised)
+    dirty_ids: np.ndarray               # int32 [n]
+    in_use_ids: np.ndarray = field(default_factory=lambda: np.empty(0, np.int32))
+    pool_seed: np.random.SeedSequence | None = None
+
+    @property
+    def batch(self) -> int:
+        return len(self.context_lens)
+
+    @property
+    def max_blocks_per_seq(self) -> int:
+        return self.block_table.shape[1]
+
+    @property
+    def max_context_len(self) -> int:
+        return int(self.context_lens.max()) if len(self.context_lens) else 0
+
+    @property
+    def kv_bytes(self) -> int:
+        """Bytes of cached K and V that one decode step has to read (valid tokens only)."""
+        return int(self.context_lens.astype(np.int64).sum()) * self.geom.kv_bytes_per_token
+
+    @property
+    def pool_shape(self):
+        g = self.geom
+        return (self.num_blocks, 2, g.num_kv_heads, g.block_size, g.head_dim)
+
+
+def blocks_needed(context_lens: np.ndarray, block_size: int) -> np.ndarray:
+    return (context_lens.astype(np.int64) + block_size - 1) // block_size
+
+
+def deal_block_table(context_lens, block_size, max_blocks_per_seq, phys_ids) -> np.ndarray:
+    """Deal physical ids to sequences in order: sequence b gets the next nb_b ids."""
+    nb = blocks_needed(context_lens, block_size)
+    if nb.max(initial=0) > max_blocks_per_seq or nb.sum() > len(phys_ids):
+        raise ValueError("block table row or id supply too small")
+    table = np.full((len(context_lens), max_blocks_per_seq), -1, dtype=np.int32)
+    pos = 0
+    for b, n in enumerate(nb):
+        table[b, :n] = phys_ids[pos:pos + n]
+        pos += n
+    return table
+
+
+def make_decode_case(name, seed, geom: Geometry, context_lens, *, num_blocks=None,
+                     max_blocks_per_seq=None, pool_factor=1.25, dirty="last",
+                     n_dirty=None, materialise_pool=True, phys_id_source=None) -> DecodeCase:
+    """Build a decode case from given context lengths.
+
+    Random sub-streams are spawned from ``seed`` in a fixed order: permutation,
+    q, pool, dirty list.  ``dirty`` selects the dirty-block list: "last" (the
+    block holding each sequence's newest token), "fraction" (n_dirty distinct
+    in-use blocks), "any" (n_dirty distinct ids from the whole pool).
+    """
+    ss_perm, ss_q, ss_pool, ss_dirty = np.random.SeedSequence(seed).spawn(4)
+    context_lens = np.asarray(context_lens, dtype=np.int32)
+    nb = blocks_needed(context_lens, geom.block_size)
+    needed = int(nb.sum())
+    if num_blocks is None:
+        num_blocks = max(1, math.ceil(pool_factor * needed))
+    if max_blocks_per_seq is None:
+        max_blocks_per_seq = max(1, int(nb.max(initial=1)))
+    if phys_id_source is None:
+        perm = np.random.default_rng(ss_perm).permutation(num_blocks).astype(np.int32)
+    else:
+        src = np.asarray(phys_id_source, dtype=np.int32)
+        perm = src[np.random.default_rng(ss_perm).permutation(len(src))]
+    in_use = perm[:needed].copy()
+    table = deal_block_table(context_lens, geom.block_size, max_blocks_per_seq, in_use)
+    q = normal_bf16(ss_q, (len(context_lens), geom.num_q_heads, geom.head_dim))
+    pool = None
+    if materialise_pool:
+        pool = normal_bf16(ss_pool, (num_blocks, 2, geom.num_kv_heads, geom.block_size, geom.head_dim))
+    rng_d = np.random.default_rng(ss_dirty)
+    if dirty == "last":
+        dirty_ids = np.array([table[b, n - 1] for b, n in enumerate(nb) if n > 0], dtype=np.int32)
+    elif dirty == "fraction":
+        dirty_ids = rng_d.choice(in_use, size=int(n_dirty), replace=False).astype(np.int32)
+    elif dirty == "any":
+        dirty_ids = rng_d.choice(num_blocks, size=int(n_dirty), replace=False).astype(np.int32)
+    else:
+        raise ValueError(dirty)
+    return DecodeCase(name, geom, context_lens, table, int(num_blocks), q, pool, dirty_ids,
+                      in_use, ss_pool)
+
+
+def _uniform_lens(seed, batch, lo, hi) -> np.ndarray:
+    """Integers uniform on [lo, hi], both ends included."""
+    ss = np.random.SeedSequence([seed, 0x6C656E])
+    return np.random.default_rng(ss).integers(lo, hi + 1, size=batch).astype(np.int32)
+
+
+def _lognormal_lens(seed, batch, median, sigma, lo, hi) -> np.ndarray:
+    ss = np.random.SeedSequence([seed, 0x6C656E])
+    z = np.random.default_rng(ss).standard_normal(batch)
+    return np.clip(np.rint(np.exp(math.log(median) + sigma * z)), lo, hi).astype(np.int32)
+
+
+# ----------------------------------------------------------------------------------------------
+# The five serving-shaped cases.  ``shrink`` divides the context-length range (and nothing else)
+# so that the CPU oracle can cover a case completely in seconds; shrink=1 is the full size.
+# ----------------------------------------------------------------------------------------------
+
+def tiny(seed=0) -> DecodeCase:
+    g = Geometry(8, 2, 64, 16)
+    lens = _uniform_lens(seed, 4, 1, 256)
+    return make_decode_case("tiny", seed, g, lens, num_blocks=128, max_blocks_per_seq=16,
+                            dirty="any", n_dirty=32)
+
+
+def llama8b_layer(seed=1, shrink=1) -> DecodeCase:
+    g = Geometry(32, 8, 128, 16)
+    lens = _uniform_lens(seed, 32, 512 // shrink, 4096 // shrink)
+    return make_decode_case("llama8b_layer", seed, g, lens, max_blocks_per_seq=256 // shrink,
+                            dirty="last")
+
+
+def long_context(seed=2, shrink=1, materialise_pool=True) -> DecodeCase:
+    g = Geometry(32, 8, 128, 16)
+    lens = _uniform_lens(seed, 8, 16384 // shrink, 65536 // shrink)
+    needed = int(blocks_needed(lens, g.block_size).sum())
+    return make_decode_case("long_context", seed, g, lens, max_blocks_per_seq=4096 // shrink,
+                            dirty="fraction", n_dirty=round(0.10 * needed),
+                            materialise_pool=materialise_pool)
+
+
+def replication_mix(seed=3, shrink=1, batch=128) -> DecodeCase:
+    g = Geometry(64, 8, 128, 32)
+    lens = _lognormal_lens(seed, batch, 1024 // shrink, 1.0, 16, 32768 // shrink)
+    return make_decode_case("replication_mix", seed, g, lens, max_blocks_per_seq=1024 // shrink,
+                            dirty="last")
+
+
+@dataclass
+class RecoveryCase:
+    """A full replica to restore into a freshly shuffled pool, then a decode over it."""
+    name: str
+    geom: Geometry
+    num_blocks: int
+    restore_ids: np.ndarray             # int32 [num_blocks], a permutation: replica[i] -> pool[ids[i]]
+    replica_seed: np.random.SeedSequence
+    decode: DecodeCase                  # pool not materialised: it is the restored pool
+
+    def replica_chunk(self, first_block: int, n_blocks: int) -> np.ndarray:
+        """Blocks [first_block, first_block+n_blocks) of the replica, uint16 [n][2][Hkv][bs][D].
+
+        Each run of REPLICA_CHUNK_BLOCKS blocks comes from its own child generator, so chunks
+        can be produced independently and in any order.
+        """
+        g = self.geom
+        cb = REPLICA_CHUNK_BLOCKS
+        if first_block % cb:
+            raise ValueError("first_block must be a multiple of REPLICA_CHUNK_BLOCKS")
+        n_chunks = -(-self.num_blocks // cb)
+        children = self.replica_seed.spawn(n_chunks)
+        out = np.empty((n_blocks, 2, g.num_kv_heads, g.block_size, g.head_dim), dtype=np.uint16)
+        lo = first_block
+
+        def fill(c):
+            a = c * cb
+            z = min(self.num_blocks, a + cb, first_block + n_blocks)
+            rng = np.random.default_rng(children[c])
+            x = rng.standard_normal((min(self.num_blocks, a + cb) - a) * g.block_elems, dtype=np.float32)
+            out[a - lo:z - lo] = f32_to_bf16_bits(x).reshape((-1,) + out.shape[1:])[:z - a]
+
+        chunks = range(first_block // cb, -(-(first_block + n_blocks) // cb))
+        with ThreadPoolExecutor(_GEN_THREADS) as ex:
+            list(ex.map(fill, chunks))
+        return out
+
+
+REPLICA_CHUNK_BLOCKS = 256
+
+
+def recovery(seed=4, num_blocks=200_000, shrink=1, batch=64) -> RecoveryCase:
+    g = Geometry(64, 8, 128, 16)
+    ss_ids, ss_rep = np.random.SeedSequence([seed, 0x726563]).spawn(2)
+    restore_ids = np.random.default_rng(ss_ids).permutation(num_blocks).astype(np.int32)
+    lens = _uniform_lens(seed, batch, 1024 // shrink, 8192 // shrink)
+    dec = make_decode_case("recovery_decode", seed, g, lens, num_blocks=num_blocks,
+                           max_blocks_per_seq=512 // shrink, dirty="last",
+                           materialise_pool=False, phys_id_source=restore_ids)
+    return RecoveryCase("recovery", g, num_blocks, restore_ids, ss_rep, dec)
+
+
+def materialise_recovered_pool(case: RecoveryCase, first_block=0, n_blocks=None) -> np.ndarray:
+    """The pool a correct restore produces, built by plain numpy indexing (for small cases)."""
+    n_blocks = case.num_blocks if n_blocks is None else n_blocks
+    g = case.geom
+    pool = np.zeros((case.num_blocks, 2, g.num_kv_heads, g.block_size, g.head_dim), dtype=np.uint16)
+    pool[case.restore_ids[first_block:first_block + n_blocks]] = case.replica_chunk(first_block, n_blocks)
+    return pool

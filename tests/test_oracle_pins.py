@@ -1,0 +1,341 @@
+"""Pins of the CPU oracle against things other than itself (no GPU).
+
+The paper gives no worked example for this path, so the oracle is held by: an independently written
+contiguous-layout attention (numpy), a library routine (torch SDPA, fp64), closed forms, invariants
+and brute-force copies.  Each pin is chosen so that one plausible mistake in the oracle (wrong head
+mapping, wrong slot index, missing normalisation, swapped K/V, wrong list order ...) fails it.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2601_22438_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def small_case(seed=7, B=3, Hq=8, Hkv=2, D=64, bs=16, lens=(1, 37, 80), NB=40):
+    g = W.Geometry(Hq, Hkv, D, bs)
+    return W.make_decode_case("small", seed, g, np.array(lens[:B], np.int32), num_blocks=NB,
+                              max_blocks_per_seq=8, dirty="any", n_dirty=10)
+
+
+def gather_contiguous(case):
+    """K, V of every sequence as float64 [L][Hkv][D], walked through the block table."""
+    g = case.geom
+    pool = W.bf16_bits_to_f32(case.pool).astype(np.float64)
+    ks, vs = [], []
+    for b, L in enumerate(case.context_lens):
+        nb = -(-int(L) // g.block_size)
+        blocks = pool[case.block_table[b, :nb]]                     # [nb][2][Hkv][bs][D]
+        k = blocks[:, 0].transpose(0, 2, 1, 3).reshape(nb * g.block_size, g.num_kv_heads, g.head_dim)[:L]
+        v = blocks[:, 1].transpose(0, 2, 1, 3).reshape(nb * g.block_size, g.num_kv_heads, g.head_dim)[:L]
+        ks.append(k)
+        vs.append(v)
+    return ks, vs
+
+
+def brute_force(case, scale=None):
+    g = case.geom
+    scale = float(np.float32(g.scale if scale is None else scale))
+    q = W.bf16_bits_to_f32(case.q).astype(np.float64)
+    ks, vs = gather_contiguous(case)
+    out = np.zeros(q.shape)
+    for b in range(case.batch):
+        if case.context_lens[b] == 0:
+            continue
+        k = np.repeat(ks[b], g.group, axis=1)                       # [L][Hq][D]
+        v = np.repeat(vs[b], g.group, axis=1)
+        s = np.einsum("hd,lhd->hl", q[b], k) * scale
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        out[b] = np.einsum("hl,lhd->hd", p, v)
+    return out
+
+
+def run_oracle(oracle, case, **kw):
+    return oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, case.geom.scale, **kw)
+
+
+# P1 ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("geom", [(8, 2, 64, 16), (4, 4, 128, 16), (16, 2, 128, 32), (6, 3, 64, 16)])
+def test_matches_contiguous_brute_force(oracle, geom):
+    Hq, Hkv, D, bs = geom
+    case = small_case(seed=11, Hq=Hq, Hkv=Hkv, D=D, bs=bs, lens=(5, bs, 3 * bs + 1))
+    np.testing.assert_allclose(run_oracle(oracle, case), brute_force(case), rtol=0, atol=1e-12)
+
+
+def test_tiny_config_matches_brute_force(oracle):
+    case = W.tiny()
+    np.testing.assert_allclose(run_oracle(oracle, case), brute_force(case), rtol=0, atol=1e-12)
+
+
+# P2 ------------------------------------------------------------------------------------------
+def test_matches_torch_sdpa_fp64(oracle):
+    import torch
+    case = small_case(seed=3, lens=(9, 64, 100))
+    g = case.geom
+    got = run_oracle(oracle, case)
+    ks, vs = gather_contiguous(case)
+    q = torch.from_numpy(W.bf16_bits_to_f32(case.q).astype(np.float64))
+    for b in range(case.batch):
+        k = torch.from_numpy(ks[b]).permute(1, 0, 2).repeat_interleave(g.group, dim=0)   # [Hq][L][D]
+        v = torch.from_numpy(vs[b]).permute(1, 0, 2).repeat_interleave(g.group, dim=0)
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            q[b][:, None, :], k, v, scale=float(np.float32(g.scale)))[:, 0]
+        np.testing.assert_allclose(got[b], ref.numpy(), rtol=0, atol=1e-12)
+
+
+# P3 ------------------------------------------------------------------------------------------
+def test_single_token_context_returns_v_exactly(oracle):
+    case = small_case(seed=5, lens=(1, 1, 1))
+    g = case.geom
+    got = run_oracle(oracle, case)
+    v = W.bf16_bits_to_f32(case.pool).astype(np.float64)
+    for b in range(case.batch):
+        p = case.block_table[b, 0]
+        for h in range(g.num_q_heads):
+            assert np.array_equal(got[b, h], v[p, 1, h // g.group, 0])
+
+
+# P4 ------------------------------------------------------------------------------------------
+def test_equal_scores_return_mean_of_v(oracle):
+    case = small_case(seed=9, lens=(33, 50, 16))
+    case.q[:] = 0                                                   # every score is 0
+    got = run_oracle(oracle, case)
+    _, vs = gather_contiguous(case)
+    for b in range(case.batch):
+        mean = np.repeat(vs[b].mean(axis=0), case.geom.group, axis=0)
+        np.testing.assert_allclose(got[b], mean, rtol=1e-14, atol=1e-15)
+
+
+def test_identical_keys_return_mean_of_v(oracle):
+    case = small_case(seed=10, lens=(20, 41, 7))
+    g = case.geom
+    for b in range(case.batch):                                     # every key of a sequence = its first key
+        first = case.pool[case.block_table[b, 0], 0, :, 0].copy()
+        nb = -(-int(case.context_lens[b]) // g.block_size)
+        case.pool[case.block_table[b, :nb], 0] = first[None, :, None, :]
+    got = run_oracle(oracle, case)
+    _, vs = gather_contiguous(case)
+    for b in range(case.batch):
+        mean = np.repeat(vs[b].mean(axis=0), g.group, axis=0)
+        np.testing.assert_allclose(got[b], mean, rtol=1e-13, atol=1e-14)
+
+
+# two-key softmax is the logistic function (stored decimal values) ------------------------------
+def test_two_keys_give_logistic_weights(oracle):
+    rows = json.load(open(os.path.join(GOLDEN, "two_key_sigmoid.json")))["rows"]
+    g = W.Geometry(2, 1, 64, 16)
+    for row in rows:
+        gap = float(row["gap"])
+        sig = float(row["sigmoid"])
+        q = np.zeros((1, 2, 64), np.float32)
+        q[0, :, 3] = 1.0                                            # picks channel 3 of the keys
+        pool = np.zeros((2, 2, 1, 16, 64), np.float32)
+        pool[1, 0, 0, 0, 3] = 0.0                                   # key 0 -> score 0
+        pool[1, 0, 0, 1, 3] = gap                                   # key 1 -> score gap (scale 1)
+        pool[1, 1, 0, 0, :] = 2.0                                   # V0
+        pool[1, 1, 0, 1, :] = -4.0                                  # V1
+        pool[0] = np.nan                                            # the other block is never used
+        out = oracle.decode_attn(W.f32_to_bf16_bits(q), W.f32_to_bf16_bits(pool),
+                                 np.array([[1]], np.int32), np.array([2], np.int32), 1.0)
+        expect = 2.0 * (1.0 - sig) - 4.0 * sig
+        np.testing.assert_allclose(out, expect, rtol=1e-15, atol=0)
+    assert g.group == 2
+
+
+# P5 ------------------------------------------------------------------------------------------
+def test_invariant_under_physical_block_permutation(oracle):
+    case = small_case(seed=21, lens=(17, 90, 128))
+    base = run_oracle(oracle, case)
+    perm = np.random.default_rng(1).permutation(case.num_blocks)    # old id -> new id
+    pool2 = np.empty_like(case.pool)
+    pool2[perm] = case.pool
+    table2 = np.where(case.block_table >= 0, perm[np.maximum(case.block_table, 0)], -1).astype(np.int32)
+    moved = oracle.decode_attn(case.q, pool2, table2, case.context_lens, case.geom.scale)
+    assert np.array_equal(base, moved)
+
+
+# P6 ------------------------------------------------------------------------------------------
+def test_pack_then_restore_same_ids_is_identity(oracle):
+    case = small_case(seed=23)
+    ids = case.dirty_ids
+    replica = oracle.pack_blocks(case.pool, ids)
+    pool2 = case.pool.copy()
+    pool2[ids] = 0
+    oracle.restore_blocks(pool2, replica, ids)
+    assert np.array_equal(pool2, case.pool)
+
+
+def test_recovery_round_trip_keeps_decode_output(oracle):
+    case = small_case(seed=25, lens=(30, 77, 128))
+    base = run_oracle(oracle, case)
+    ids = case.in_use_ids
+    replica = oracle.pack_blocks(case.pool, ids)
+    rng = np.random.default_rng(2)
+    new_ids = rng.permutation(case.num_blocks)[:len(ids)].astype(np.int32)
+    fresh = np.full_like(case.pool, 0x7FC0)                         # target pool starts as NaN patterns
+    oracle.restore_blocks(fresh, replica, new_ids)
+    remap = np.full(case.num_blocks, -1, np.int32)
+    remap[ids] = new_ids
+    table2 = np.where(case.block_table >= 0, remap[np.maximum(case.block_table, 0)], -1).astype(np.int32)
+    after = oracle.decode_attn(case.q, fresh, table2, case.context_lens, case.geom.scale)
+    assert np.array_equal(base, after)
+
+
+# P7 ------------------------------------------------------------------------------------------
+def test_shift_of_all_keys_leaves_output_unchanged(oracle):
+    # Keys are small integers and the shift is an integer vector, so shifted keys stay exact in bf16.
+    case = small_case(seed=27, lens=(12, 40, 66))
+    rng = np.random.default_rng(3)
+    k_int = rng.integers(-3, 4, size=case.pool[:, 0].shape).astype(np.float32)
+    case.pool[:, 0] = W.f32_to_bf16_bits(k_int)
+    q_int = rng.integers(-2, 3, size=case.q.shape).astype(np.float32)
+    case.q[:] = W.f32_to_bf16_bits(q_int)
+    base = run_oracle(oracle, case)
+    c = rng.integers(-4, 5, size=(1, case.geom.num_kv_heads, 1, case.geom.head_dim)).astype(np.float32)
+    shifted = case.pool.copy()
+    shifted[:, 0] = W.f32_to_bf16_bits(k_int + c)
+    moved = oracle.decode_attn(case.q, shifted, case.block_table, case.context_lens, case.geom.scale)
+    np.testing.assert_allclose(moved, base, rtol=0, atol=1e-12)
+
+
+# P8 ------------------------------------------------------------------------------------------
+def test_dominant_key_wins(oracle):
+    case = small_case(seed=29, lens=(50, 50, 50))
+    g = case.geom
+    case.q[:] = W.f32_to_bf16_bits(np.ones(case.q.shape, np.float32))
+    case.pool[:, 0] = 0
+    t_star = 37
+    for b in range(case.batch):
+        p = case.block_table[b, t_star // g.block_size]
+        case.pool[p, 0, :, t_star % g.block_size] = W.f32_to_bf16_bits(np.full((g.num_kv_heads, g.head_dim), 8.0, np.float32))
+    got = run_oracle(oracle, case)                                  # winning score = 0.125*64*8 = 64
+    v = W.bf16_bits_to_f32(case.pool).astype(np.float64)
+    for b in range(case.batch):
+        p = case.block_table[b, t_star // g.block_size]
+        for h in range(g.num_q_heads):
+            np.testing.assert_allclose(got[b, h], v[p, 1, h // g.group, t_star % g.block_size], rtol=0, atol=1e-20 * 50 * 6)
+
+
+# P9 ------------------------------------------------------------------------------------------
+def test_partition_merge_identity(oracle):
+    """Running the oracle on chunks of the context and merging (max, sum, weighted accumulators)
+    gives the direct result: validates the split reduction formula without any GPU code."""
+    case = small_case(seed=31, B=1, lens=(128,), NB=16)
+    g = case.geom
+    direct = run_oracle(oracle, case)[0]
+    q = W.bf16_bits_to_f32(case.q).astype(np.float64)[0]
+    ks, vs = gather_contiguous(case)
+    k = np.repeat(ks[0], g.group, axis=1)
+    s_all = np.einsum("hd,lhd->hl", q, k) * float(np.float32(g.scale))
+    parts = []
+    for lo, hi in ((0, 48), (48, 64), (64, 128)):                   # chunks aligned to whole blocks
+        sub_lens = np.array([hi - lo], np.int32)
+        sub_table = case.block_table[:, lo // g.block_size:]
+        o = oracle.decode_attn(case.q, case.pool, np.ascontiguousarray(sub_table), sub_lens, g.scale)[0]
+        m = s_all[:, lo:hi].max(axis=1)
+        l = np.exp(s_all[:, lo:hi] - m[:, None]).sum(axis=1)
+        parts.append((m, l, o * l[:, None]))                        # un-normalised accumulator
+    M = np.max([p[0] for p in parts], axis=0)
+    num = sum(np.exp(m - M)[:, None] * acc for m, l, acc in parts)
+    den = sum(np.exp(m - M) * l for m, l, acc in parts)
+    np.testing.assert_allclose(num / den[:, None], direct, rtol=0, atol=1e-13)
+
+
+# P10 -----------------------------------------------------------------------------------------
+def test_unused_slots_blocks_and_table_entries_are_ignored(oracle):
+    case = small_case(seed=33, lens=(5, 37, 81))
+    g = case.geom
+    base = run_oracle(oracle, case)
+    pool = np.full_like(case.pool, 0x7FC0)                          # NaN everywhere ...
+    table = np.full_like(case.block_table, -1)
+    for b, L in enumerate(case.context_lens):
+        nb = -(-int(L) // g.block_size)
+        table[b, :nb] = case.block_table[b, :nb]
+        for j in range(nb):
+            valid = min(g.block_size, int(L) - j * g.block_size)
+            p = case.block_table[b, j]
+            pool[p, :, :, :valid] = case.pool[p, :, :, :valid]      # ... except the valid token rows
+    got = oracle.decode_attn(case.q, pool, table, case.context_lens, g.scale)
+    assert np.array_equal(got, base)
+    assert not np.isnan(got).any()
+
+
+def test_zero_length_context_gives_zero_rows(oracle):
+    case = small_case(seed=35, lens=(0, 20, 0))
+    got = run_oracle(oracle, case)
+    assert np.array_equal(got[0], np.zeros_like(got[0])) and np.array_equal(got[2], np.zeros_like(got[2]))
+    np.testing.assert_allclose(got[1], brute_force(case)[1], atol=1e-12)
+
+
+# P11 -----------------------------------------------------------------------------------------
+def test_gqa_equals_mha_with_duplicated_kv_heads(oracle):
+    case = small_case(seed=37, Hq=8, Hkv=2, lens=(10, 33, 70))
+    g = case.geom
+    got = run_oracle(oracle, case)
+    pool_mha = np.repeat(case.pool, g.group, axis=2)                # KV head kvh -> G consecutive heads
+    mha = oracle.decode_attn(case.q, pool_mha, case.block_table, case.context_lens, g.scale)
+    assert np.array_equal(got, mha)
+    # and the head mapping is "consecutive query heads share a KV head": perturbing KV head 1
+    # changes exactly query heads G .. 2G-1
+    pool2 = case.pool.copy()
+    pool2[:, 1, 1] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(pool2[:, 1, 1]) + 1.0)
+    got2 = oracle.decode_attn(case.q, pool2, case.block_table, case.context_lens, g.scale)
+    changed = np.any(got2 != got, axis=(0, 2))
+    assert changed.tolist() == [False] * g.group + [True] * g.group
+
+
+def test_scale_is_applied_to_scores(oracle):
+    case = small_case(seed=39, lens=(25, 60, 99))
+    for scale in (0.125, 0.5, 1.0):
+        got = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, scale)
+        np.testing.assert_allclose(got, brute_force(case, scale), rtol=0, atol=1e-12)
+
+
+def test_rows_subset_matches_full(oracle):
+    case = small_case(seed=41, lens=(25, 60, 99))
+    full = run_oracle(oracle, case)
+    rows = np.array([[2, 7], [0, 0], [1, 3], [2, 7]], np.int32)
+    sub = run_oracle(oracle, case, rows=rows)
+    assert np.array_equal(sub, full[rows[:, 0], rows[:, 1]])
+    one = run_oracle(oracle, case, num_threads=1)
+    assert np.array_equal(one, full)
+
+
+# P12 -----------------------------------------------------------------------------------------
+def test_pack_restore_match_numpy_indexing(oracle):
+    case = small_case(seed=43)
+    rng = np.random.default_rng(5)
+    ids = rng.integers(0, case.num_blocks, size=25).astype(np.int32)          # repeats allowed for pack
+    assert np.array_equal(oracle.pack_blocks(case.pool, ids), case.pool[ids])
+    ids_d = rng.permutation(case.num_blocks)[:13].astype(np.int32)
+    replica = W.normal_bf16(np.random.SeedSequence(6), (13,) + case.pool.shape[1:])
+    expect = case.pool.copy()
+    expect[ids_d] = replica
+    got = case.pool.copy()
+    oracle.restore_blocks(got, replica, ids_d)
+    assert np.array_equal(got, expect)
+    untouched = np.setdiff1d(np.arange(case.num_blocks), ids_d)
+    assert np.array_equal(got[untouched], case.pool[untouched])
+    empty = oracle.pack_blocks(case.pool, np.empty(0, np.int32))
+    assert empty.shape == (0,) + case.pool.shape[1:]
+
+
+def test_restore_rejects_duplicates_and_bad_ids(oracle):
+    case = small_case(seed=45)
+    replica = case.pool[:2].copy()
+    with pytest.raises(oracle.OracleError):
+        oracle.restore_blocks(case.pool.copy(), replica, np.array([3, 3], np.int32))
+    with pytest.raises(oracle.OracleError):
+        oracle.restore_blocks(case.pool.copy(), replica, np.array([3, case.num_blocks], np.int32))
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_blocks(case.pool, np.array([-1], np.int32))
+    bad = case.block_table.copy()
+    bad[1, 0] = case.num_blocks
+    with pytest.raises(oracle.OracleError):
+        oracle.decode_attn(case.q, case.pool, bad, case.context_lens, 0.125)
