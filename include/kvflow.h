@@ -1,0 +1,160 @@
+/*
+ * kvflow.h - C ABI of the paged KV-cache data path for one MI355X (gfx950).
+ *
+ * The library serves the two uses the paper makes of a block-paged KV cache
+ * (Sec. 3.2 item 3, "Background KV Cache Replication"; overhead in Sec. 4.4):
+ *   1. the decode step itself: one query token per in-flight request attends to
+ *      that request's cached keys/values, stored as fixed-size blocks that a
+ *      per-request block table maps from logical to physical position;
+ *   2. block-by-block replication: the blocks a step has written are gathered
+ *      into a contiguous replica buffer on a separate stream (pack), and a
+ *      replication target scatters a replica into its own pool so that requests
+ *      continue from the replicated state (restore).
+ *
+ * General rules
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer.  The library allocates no memory, keeps no
+ *     state between calls and never synchronises: a call validates its host
+ *     arguments, enqueues kernels on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and returns.  Buffers must stay alive and
+ *     unmodified until the stream has passed the enqueued work.
+ *   - Return value: KV_OK (0) or a negative kv_status.  Host-checkable mistakes
+ *     are reported before anything is launched; nothing is written in that case.
+ *   - Contents of device arrays (block ids, context lengths) cannot be checked
+ *     without a device-to-host copy and are PRECONDITIONS, listed per call.
+ *     kv_validate_* checks them with a synchronising copy, for debugging.
+ *   - pack || decode on two streams is legal (both only read the pool);
+ *     restore -> decode needs stream order or an event.
+ *
+ * Pool layout (bf16): [num_blocks][2][num_kv_heads][block_size][head_dim],
+ * second axis 0 = K, 1 = V.  One block is one contiguous chunk of
+ * kv_block_bytes() bytes; layers are stacked as separate blocks of one flat pool.
+ */
+#ifndef KVFLOW_H
+#define KVFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KV_OK = 0,
+    KV_ERR_NULL = -1,        /* a required pointer is NULL */
+    KV_ERR_SHAPE = -2,       /* non-positive or inconsistent dimension */
+    KV_ERR_UNSUPPORTED = -3, /* dimension or dtype outside what the kernels are built for */
+    KV_ERR_ALIGN = -4,       /* a buffer is not 16-byte aligned */
+    KV_ERR_WORKSPACE = -5,   /* workspace missing or too small */
+    KV_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch */
+    KV_ERR_CONTENT = -7      /* kv_validate_*: a device array violates a precondition */
+} kv_status;
+
+enum { KV_DTYPE_BF16 = 0, KV_DTYPE_F32 = 1 };
+
+/* Host struct describing the block pool; read during the call only. */
+typedef struct {
+    void*   base;          /* device, 16-byte aligned, layout above */
+    int64_t num_blocks;    /* > 0 */
+    int32_t num_kv_heads;  /* > 0 */
+    int32_t block_size;    /* tokens per block: 16 or 32 */
+    int32_t head_dim;      /* 64 or 128 */
+    int32_t dtype;         /* KV_DTYPE_BF16 */
+} kv_pool_desc;
+
+/* Bytes of one block = 2 * num_kv_heads * block_size * head_dim * 2; 0 if pool is NULL/invalid. */
+size_t kv_block_bytes(const kv_pool_desc* pool);
+
+/*
+ * Number of tokens of one sequence that a single workgroup reduces before the
+ * partial results are merged (the split of long contexts across workgroups).
+ * partition_tokens == 0 asks for the library's choice for this problem size;
+ * the result is a multiple of 32.  Returns 0 on invalid arguments.
+ */
+int32_t kv_decode_partition_tokens(int32_t batch, int32_t num_kv_heads, int32_t max_context_len,
+                                   int32_t partition_tokens);
+
+/*
+ * Bytes of workspace kv_decode_attn needs: 0 when every context fits one
+ * partition, else batch * num_q_heads * splits * (head_dim + 2) * 4 with
+ * splits = ceil(max_context_len / partition).  partition_tokens as above.
+ */
+size_t kv_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t num_kv_heads,
+                                 int32_t head_dim, int32_t max_context_len, int32_t partition_tokens);
+
+/*
+ * Paged decode attention (Sec. 3.2 item 3: attention state kept in a
+ * block-represented KV cache).  For every sequence b and query head h, with
+ * kvh = h / (num_q_heads / num_kv_heads) and L = context_lens[b]:
+ *     s[t]   = scale * sum_d q[b,h,d] * K[table[b][t / bs], kvh, t % bs, d]     0 <= t < L
+ *     out[b,h,:] = sum_t softmax(s)[t] * V[table[b][t / bs], kvh, t % bs, :]
+ * bf16 inputs, fp32 accumulation; L == 0 gives a row of zeros.
+ *
+ *   out            [batch][num_q_heads][head_dim], out_dtype KV_DTYPE_BF16 or KV_DTYPE_F32, written
+ *   q              [batch][num_q_heads][head_dim] bf16, read
+ *   pool           host struct; the pool is read
+ *   block_table    int32 [batch][max_blocks_per_seq], read; only the first
+ *                  ceil(L/bs) entries of a row are dereferenced
+ *   context_lens   int32 [batch], read
+ *   max_context_len host-side upper bound of context_lens[]; sizes the grid and the split
+ *   partition_tokens 0 = library's choice, else a multiple of 32 (see above)
+ *   workspace      >= kv_decode_workspace_bytes(...) bytes, 16-byte aligned, scratch
+ *                  (may be NULL when that size is 0)
+ * Preconditions on device contents: 0 <= context_lens[b] <= max_context_len;
+ * 0 <= block_table[b][j] < num_blocks for j < ceil(context_lens[b] / bs).
+ * Slots past L in the last block, unreferenced table entries and unreferenced
+ * blocks are never used and may hold anything, including NaN patterns.
+ * The result depends only on logical token positions: two pools that hold the
+ * same blocks under different physical ids give bitwise equal outputs.
+ * Errors: NULL, SHAPE (dims <= 0, num_q_heads % num_kv_heads, num_q_heads /
+ * num_kv_heads > 16, max_context_len > max_blocks_per_seq * bs, partition not a
+ * multiple of 32), UNSUPPORTED (head_dim, block_size, dtypes), ALIGN, WORKSPACE,
+ * LAUNCH.  batch == 0 returns KV_OK without a launch.
+ */
+int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
+                   const int32_t* block_table, int32_t max_blocks_per_seq,
+                   const int32_t* context_lens, int32_t batch, int32_t num_q_heads,
+                   int32_t max_context_len, float scale, int32_t partition_tokens,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Gather side of block-by-block replication (Sec. 3.2 item 3; meant to run on a
+ * stream of its own beside decode, Sec. 4.4):
+ *     replica[i] <- pool[block_ids[i]]   for i in [0, n), whole blocks, list order.
+ *   replica    [n][kv_block_bytes] bytes, 16-byte aligned, written
+ *   block_ids  int32 [n], read; ids may repeat
+ * Precondition: 0 <= block_ids[i] < num_blocks.  n == 0 returns KV_OK without a launch.
+ */
+int kv_pack_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n,
+                   void* stream);
+
+/*
+ * Scatter side, used on the replication target at recovery (Sec. 3.2 item 3:
+ * requests continue from the replicated state):
+ *     pool[block_ids[i]] <- replica[i]   for i in [0, n).
+ * Blocks not listed are left untouched.
+ * Preconditions: 0 <= block_ids[i] < num_blocks and the ids are pairwise
+ * distinct (a repeated id is a write race; the result for that block is undefined).
+ */
+int kv_restore_blocks(const kv_pool_desc* pool, const void* replica, const int32_t* block_ids,
+                      int64_t n, void* stream);
+
+/*
+ * Debug helpers: copy the device arrays to the host (synchronising `stream`)
+ * and check the preconditions above.  Return KV_OK, KV_ERR_CONTENT, or an
+ * argument error.  Not for the hot path.
+ */
+int kv_validate_decode(const kv_pool_desc* pool, const int32_t* block_table,
+                       int32_t max_blocks_per_seq, const int32_t* context_lens, int32_t batch,
+                       int32_t max_context_len, void* stream);
+int kv_validate_block_ids(const kv_pool_desc* pool, const int32_t* block_ids, int64_t n,
+                          int32_t require_distinct, void* stream);
+
+/* Static, human-readable text for a kv_status value. */
+const char* kv_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVFLOW_H */

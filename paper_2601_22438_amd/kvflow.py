@@ -1,0 +1,146 @@
+"""Thin ctypes binding of libkvflow.so: argument marshalling only.
+
+Every function has the name and argument order of the C entry point it calls
+(see include/kvflow.h).  Tensors are torch CUDA tensors used as device memory;
+their ``data_ptr()`` and the current HIP stream handle are passed through.  There
+is no fallback: if the library cannot be loaded the import of any function fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+KV_DTYPE_BF16 = 0
+KV_DTYPE_F32 = 1
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvflow.so")
+_lib = None
+
+
+class KvflowError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"kvflow status {status}: {text}")
+        self.status = status
+
+
+class kv_pool_desc(ctypes.Structure):
+    _fields_ = [("base", ctypes.c_void_p), ("num_blocks", ctypes.c_int64),
+                ("num_kv_heads", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libkvflow.so (built in-tree by paper_2601_22438_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2601_22438_amd.build` first")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, I32, I64, SZ, F = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
+    PD = ctypes.POINTER(kv_pool_desc)
+    lib.kv_block_bytes.restype, lib.kv_block_bytes.argtypes = SZ, [PD]
+    lib.kv_decode_partition_tokens.restype = I32
+    lib.kv_decode_partition_tokens.argtypes = [I32, I32, I32, I32]
+    lib.kv_decode_workspace_bytes.restype = SZ
+    lib.kv_decode_workspace_bytes.argtypes = [I32, I32, I32, I32, I32, I32]
+    lib.kv_decode_attn.restype = ctypes.c_int
+    lib.kv_decode_attn.argtypes = [P, I32, P, PD, P, I32, P, I32, I32, I32, F, I32, P, SZ, P]
+    lib.kv_pack_blocks.restype = ctypes.c_int
+    lib.kv_pack_blocks.argtypes = [P, PD, P, I64, P]
+    lib.kv_restore_blocks.restype = ctypes.c_int
+    lib.kv_restore_blocks.argtypes = [PD, P, P, I64, P]
+    lib.kv_validate_decode.restype = ctypes.c_int
+    lib.kv_validate_decode.argtypes = [PD, P, I32, P, I32, I32, P]
+    lib.kv_validate_block_ids.restype = ctypes.c_int
+    lib.kv_validate_block_ids.argtypes = [PD, P, I64, I32, P]
+    lib.kv_status_string.restype, lib.kv_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def kv_status_string(status: int) -> str:
+    return load().kv_status_string(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise KvflowError(status, kv_status_string(status))
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def pool_desc(pool: torch.Tensor) -> kv_pool_desc:
+    """Describe a pool tensor of shape [NB][2][Hkv][bs][D] (bf16, contiguous, on the GPU)."""
+    if pool.dim() != 5 or pool.shape[1] != 2 or not pool.is_contiguous():
+        raise ValueError("pool must be a contiguous [NB][2][Hkv][bs][D] tensor")
+    if pool.dtype != torch.bfloat16:
+        raise ValueError("pool must be bfloat16")
+    nb, _, hkv, bs, d = pool.shape
+    return kv_pool_desc(pool.data_ptr(), nb, hkv, bs, d, KV_DTYPE_BF16)
+
+
+def kv_block_bytes(pool: torch.Tensor) -> int:
+    return int(load().kv_block_bytes(ctypes.byref(pool_desc(pool))))
+
+
+def kv_decode_partition_tokens(batch, num_kv_heads, max_context_len, partition_tokens=0) -> int:
+    return int(load().kv_decode_partition_tokens(batch, num_kv_heads, max_context_len, partition_tokens))
+
+
+def kv_decode_workspace_bytes(batch, num_q_heads, num_kv_heads, head_dim, max_context_len,
+                              partition_tokens=0) -> int:
+    return int(load().kv_decode_workspace_bytes(batch, num_q_heads, num_kv_heads, head_dim,
+                                                max_context_len, partition_tokens))
+
+
+def kv_decode_attn(out, q, pool, block_table, context_lens, max_context_len, scale,
+                   partition_tokens=0, workspace=None, stream=None) -> None:
+    """Enqueue paged decode attention; ``out`` ([B][Hq][D], bf16 or fp32) is written in place."""
+    batch, num_q_heads, _ = q.shape
+    out_dtype = {torch.bfloat16: KV_DTYPE_BF16, torch.float32: KV_DTYPE_F32}[out.dtype]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().kv_decode_attn(
+        _ptr(out), out_dtype, _ptr(q), ctypes.byref(pool_desc(pool)), _ptr(block_table),
+        block_table.shape[1], _ptr(context_lens), batch, num_q_heads, int(max_context_len),
+        float(scale), int(partition_tokens), _ptr(workspace), ws_bytes, _stream_handle(stream)))
+
+
+def kv_pack_blocks(replica, pool, block_ids, n=None, stream=None) -> None:
+    """Enqueue replica[i] <- pool[block_ids[i]] for i < n (default: all of block_ids)."""
+    n = block_ids.numel() if n is None else int(n)
+    _check(load().kv_pack_blocks(_ptr(replica), ctypes.byref(pool_desc(pool)), _ptr(block_ids), n,
+                                 _stream_handle(stream)))
+
+
+def kv_restore_blocks(pool, replica, block_ids, n=None, stream=None) -> None:
+    """Enqueue pool[block_ids[i]] <- replica[i] for i < n (ids pairwise distinct)."""
+    n = block_ids.numel() if n is None else int(n)
+    _check(load().kv_restore_blocks(ctypes.byref(pool_desc(pool)), _ptr(replica), _ptr(block_ids), n,
+                                    _stream_handle(stream)))
+
+
+def kv_validate_decode(pool, block_table, context_lens, max_context_len, stream=None) -> int:
+    return int(load().kv_validate_decode(
+        ctypes.byref(pool_desc(pool)), _ptr(block_table), block_table.shape[1], _ptr(context_lens),
+        context_lens.numel(), int(max_context_len), _stream_handle(stream)))
+
+
+def kv_validate_block_ids(pool, block_ids, require_distinct=False, stream=None) -> int:
+    return int(load().kv_validate_block_ids(
+        ctypes.byref(pool_desc(pool)), _ptr(block_ids), block_ids.numel(), int(bool(require_distinct)),
+        _stream_handle(stream)))
