@@ -1,0 +1,364 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged KV-cache data path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input, all inputs
+resident in HBM: paged decode attention over the batch (partition kernel + merge kernel), then
+pack of the step's dirty blocks into a contiguous replica, then restore of a replica (the one
+packed a step earlier) into a second pool under fresh block ids.  The timed workload is the
+long-context case (the largest decode working set); the other cases are reported under "extra":
+a full 200k-block restore and pack (the copy-bandwidth figure), the replication mix with pack on a
+side stream beside decode (overlap cost), and the 8B-layer case (cache-resident, latency only).
+
+Prints ONE JSON line.  `value` is decode KV bytes per second: valid cached tokens x K/V bytes per
+token, divided by the mean time of the decode call measured with HIP events inside the timed steps.
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+# HBM traffic per decode launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
+# WRITE_SIZE), scaled by the same counters on a plain copy of known size; see profiles/.  Valid
+# only for the kernel source the counters were taken with.
+DECODE_TRAFFIC = {"kernel_sha256": None, "fetch_bytes": None, "write_bytes": None}
+
+PAPER_CONTEXT = {
+    "note": "end-to-end serving figures from the paper, other hardware, context only",
+    "hardware": "8/16 nodes, one NVIDIA A10 24GB per node, 1 Gbps Ethernet, Llama-3.1-8B, 4-stage pipeline",
+    "mttr_s": [35, 30, 29], "mttr_baseline_s": 600,
+    "tpot_ms_avg_p99": [163, 203],
+    "best_avg_latency_improvement": 3.12, "best_p99_latency_improvement": 2.85,
+    "best_avg_ttft_improvement": 378.91, "best_p99_ttft_improvement": 574.56,
+    "replication_overhead_pct_avg_p99": {"8_nodes": [2.3, 2.8], "16_nodes": [4.0, 3.6]},
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def bf16_dev(bits):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+class Decode:
+    """Device-resident inputs of one decode case plus its output and workspace."""
+
+    def __init__(self, case, pool, kvflow, out_dtype=None):
+        import torch
+        g = case.geom
+        self.case, self.kvflow, self.pool = case, kvflow, pool
+        self.q = bf16_dev(case.q)
+        self.table = torch.from_numpy(case.block_table).cuda()
+        self.lens = torch.from_numpy(case.context_lens).cuda()
+        self.out = torch.empty((case.batch, g.num_q_heads, g.head_dim), device="cuda",
+                               dtype=out_dtype or torch.bfloat16)
+        self.max_len = case.max_context_len
+        nbytes = kvflow.kv_decode_workspace_bytes(case.batch, g.num_q_heads, g.num_kv_heads, g.head_dim,
+                                                  self.max_len, 0)
+        self.ws = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device="cuda") if nbytes else None
+        self.partition = kvflow.kv_decode_partition_tokens(case.batch, g.num_kv_heads, self.max_len, 0)
+        self.scale = float(g.scale)
+
+    def run(self, stream=None):
+        self.kvflow.kv_decode_attn(self.out, self.q, self.pool, self.table, self.lens, self.max_len,
+                                   self.scale, 0, self.ws, stream)
+
+
+def event_ms(pairs):
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def stats(ms):
+    a = np.asarray(ms, dtype=np.float64)
+    return {"mean_ms": float(a.mean()), "median_ms": float(np.median(a)), "min_ms": float(a.min())}
+
+
+def time_calls(fn, iters, warmup):
+    """Mean/median/min duration of fn() on the current stream, one HIP event pair per call."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    pairs = []
+    for _ in range(iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    return stats(event_ms(pairs))
+
+
+def copy_rates(payload_bytes, ms):
+    gbps = payload_bytes / (ms * 1e-3) / 1e9
+    return {"payload_GBps": gbps, "traffic_GBps": 2 * gbps, "frac_hbm_peak": 2 * gbps / HBM_PEAK_GBPS}
+
+
+def bench_long_context(args, kvflow, W):
+    """The timed workload: K steps of decode -> pack -> restore on one stream."""
+    import torch
+    t0 = time.time()
+    case = W.long_context()
+    g = case.geom
+    log(f"[bench] long_context generated in {time.time() - t0:.1f}s: lens={case.context_lens.tolist()} "
+        f"pool={case.num_blocks} blocks, dirty={len(case.dirty_ids)}")
+    pool = bf16_dev(case.pool)
+    dec = Decode(case, pool, kvflow)
+    n = len(case.dirty_ids)
+    ids = torch.from_numpy(case.dirty_ids).cuda()
+    replicas = [torch.empty((n,) + pool.shape[1:], dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    # the recovery target: a second pool and fresh ids for the restored blocks
+    target = torch.empty_like(pool)
+    fresh = np.random.default_rng(12345).permutation(case.num_blocks)[:n].astype(np.int32)
+    fresh_ids = torch.from_numpy(fresh).cuda()
+    kvflow.kv_pack_blocks(replicas[1], pool, ids)          # the replica the first restore consumes
+
+    def step(i, evs=None):
+        if evs is not None:
+            evs[0].record()
+        dec.run()
+        if evs is not None:
+            evs[1].record()
+        kvflow.kv_pack_blocks(replicas[i & 1], pool, ids)
+        if evs is not None:
+            evs[2].record()
+        kvflow.kv_restore_blocks(target, replicas[(i + 1) & 1], fresh_ids)
+        if evs is not None:
+            evs[3].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    all_evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, all_evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    d_ms = stats([e[0].elapsed_time(e[1]) for e in all_evs])
+    p_ms = stats([e[1].elapsed_time(e[2]) for e in all_evs])
+    r_ms = stats([e[2].elapsed_time(e[3]) for e in all_evs])
+    kv_bytes = case.kv_bytes
+    payload = n * g.block_bytes
+    res = {
+        "case": case, "dec": dec, "pool": pool, "ids": ids, "replica": replicas[0],
+        "ms_per_step": wall / args.steps * 1e3,
+        "decode": d_ms, "pack": p_ms, "restore": r_ms,
+        "kv_bytes": kv_bytes, "payload": payload,
+        "decode_GBps": kv_bytes / (d_ms["mean_ms"] * 1e-3) / 1e9,
+    }
+    return res
+
+
+def cpu_baseline(case, oracle, n_seqs=2):
+    """The oracle as it stands, timed on this host: all query heads of the first n_seqs sequences."""
+    g = case.geom
+    rows = np.array([(b, h) for b in range(n_seqs) for h in range(g.num_q_heads)], np.int32)
+    t0 = time.perf_counter()
+    _, threads = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale,
+                                    rows=rows, return_threads=True)
+    dt = time.perf_counter() - t0
+    sample_bytes = int(case.context_lens[:n_seqs].astype(np.int64).sum()) * g.kv_bytes_per_token
+    t0 = time.perf_counter()
+    rep, _ = oracle.pack_blocks(case.pool, case.dirty_ids, return_threads=True)
+    dt_pack = time.perf_counter() - t0
+    return {
+        "value": sample_bytes / dt / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"fp64 decode of all {g.num_q_heads} query heads of the first {n_seqs} of {case.batch} "
+                  f"sequences of the timed workload ({sample_bytes / 1e6:.0f} MB of KV, {dt:.1f} s); "
+                  f"pack of the full dirty list by memcpy: {rep.nbytes / dt_pack / 1e9:.2f} GB/s payload",
+        "seconds": dt, "pack_payload_GBps": rep.nbytes / dt_pack / 1e9,
+        "cpu_model": cpu_model(), "host_cores": os.cpu_count(),
+    }
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def bench_recovery(args, kvflow, W, num_blocks):
+    """Full-replica restore (and the symmetric pack) of num_blocks 64 KiB blocks, then a decode."""
+    import torch
+    t0 = time.time()
+    rc = W.recovery(num_blocks=num_blocks)
+    g = rc.geom
+    shape = (num_blocks, 2, g.num_kv_heads, g.block_size, g.head_dim)
+    replica = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    step = 16 * W.REPLICA_CHUNK_BLOCKS
+    for first in range(0, num_blocks, step):
+        nb = min(step, num_blocks - first)
+        replica[first:first + nb] = bf16_dev(rc.replica_chunk(first, nb))
+    log(f"[bench] recovery replica ({num_blocks} blocks, {replica.numel() * 2 / 1e9:.2f} GB) generated "
+        f"and uploaded in {time.time() - t0:.1f}s")
+    pool = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    ids = torch.from_numpy(rc.restore_ids).cuda()
+    payload = num_blocks * g.block_bytes
+    r = time_calls(lambda: kvflow.kv_restore_blocks(pool, replica, ids), args.copy_iters, 2)
+    back = torch.empty_like(replica)
+    p = time_calls(lambda: kvflow.kv_pack_blocks(back, pool, ids), args.copy_iters, 2)
+    same = bool(torch.equal(back, replica))
+    del back
+    dec = Decode(rc.decode, pool, kvflow)
+    d = time_calls(dec.run, 10, 3)
+    out = {
+        "blocks": num_blocks, "payload_GB": payload / 1e9,
+        "restore": {**r, **copy_rates(payload, r["mean_ms"])},
+        "pack": {**p, **copy_rates(payload, p["mean_ms"])},
+        "pack_of_restore_is_identity": same,
+        "decode_after_restore": {**d, "kv_GB": rc.decode.kv_bytes / 1e9, "partition_tokens": dec.partition,
+                                 "kv_GBps": rc.decode.kv_bytes / (d["mean_ms"] * 1e-3) / 1e9,
+                                 "frac_hbm_peak": rc.decode.kv_bytes / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+    }
+    # plain device-to-device copy of the same bytes, as a yardstick of what a copy reaches here
+    dst = torch.empty_like(replica)
+    c = time_calls(lambda: dst.copy_(replica), args.copy_iters, 2)
+    out["plain_copy_same_bytes"] = {**c, **copy_rates(payload, c["mean_ms"])}
+    return out
+
+
+def bench_replication_mix(args, kvflow, W):
+    """Decode alone, pack alone, and pack on a side stream beside decode."""
+    import torch
+    case = W.replication_mix()
+    g = case.geom
+    pool = bf16_dev(case.pool)
+    dec = Decode(case, pool, kvflow)
+    ids = torch.from_numpy(case.dirty_ids).cuda()
+    n = len(case.dirty_ids)
+    replica = torch.empty((n,) + pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+    d = time_calls(dec.run, 20, 5)
+    p = time_calls(lambda: kvflow.kv_pack_blocks(replica, pool, ids), 20, 5)
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    fork, join = torch.cuda.Event(), torch.cuda.Event()
+
+    def both():
+        fork.record(main)
+        side.wait_event(fork)
+        kvflow.kv_pack_blocks(replica, pool, ids, stream=side)
+        dec.run()
+        join.record(side)
+        main.wait_event(join)
+
+    o = time_calls(both, 20, 5)
+    kv = case.kv_bytes
+    return {
+        "kv_GB": kv / 1e9, "dirty_blocks": n, "pack_payload_MB": n * g.block_bytes / 1e6,
+        "partition_tokens": dec.partition,
+        "decode_alone": {**d, "kv_GBps": kv / (d["mean_ms"] * 1e-3) / 1e9,
+                         "frac_hbm_peak": kv / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "pack_alone": {**p, **copy_rates(n * g.block_bytes, p["mean_ms"])},
+        "decode_with_pack_on_side_stream": o,
+        "decode_slowdown_pct": 100.0 * (o["mean_ms"] / d["mean_ms"] - 1.0),
+    }
+
+
+def bench_llama_layer(args, kvflow, W):
+    case = W.llama8b_layer()
+    pool = bf16_dev(case.pool)
+    dec = Decode(case, pool, kvflow)
+    d = time_calls(dec.run, 50, 10)
+    kv = case.kv_bytes
+    return {"kv_GB": kv / 1e9, "partition_tokens": dec.partition, **d,
+            "kv_GBps": kv / (d["mean_ms"] * 1e-3) / 1e9,
+            "note": "working set near the last-level cache size: latency figure, not an HBM measurement"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--copy-iters", type=int, default=5)
+    ap.add_argument("--recovery-blocks", type=int, default=200_000)
+    ap.add_argument("--only-timed", action="store_true", help="skip the extra cases and the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU only: this data path uses no second GPU; run with --gpus 1")
+
+    import torch
+    from paper_2601_22438_amd import kvflow
+    from paper_2601_22438_amd import workloads as W
+    kvflow.load()                                     # fails loudly when the HIP library is missing
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+
+    main_res = bench_long_context(args, kvflow, W)
+    case = main_res["case"]
+    g = case.geom
+    d = main_res["decode"]
+    achieved = main_res["decode_GBps"]
+    src = open(os.path.join(ROOT, "paper_2601_22438_amd", "csrc", "kv_decode.hip"), "rb").read()
+    traffic = None
+    if DECODE_TRAFFIC["kernel_sha256"] == hashlib.sha256(src).hexdigest():
+        traffic = DECODE_TRAFFIC["fetch_bytes"] + DECODE_TRAFFIC["write_bytes"]
+    roofline = {"bound": "hbm", "kernel": "decode_partition_kernel<128> + decode_merge_kernel<128> (one decode call)",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                "algorithmic_bytes_per_launch": main_res["kv_bytes"], "mean_launch_ms": d["mean_ms"]}
+    extra = {
+        "timed_workload": {
+            "decode": {**d, "kv_GBps": achieved, "frac_hbm_peak": achieved / HBM_PEAK_GBPS,
+                       "partition_tokens": main_res["dec"].partition},
+            "pack": {**main_res["pack"], **copy_rates(main_res["payload"], main_res["pack"]["mean_ms"])},
+            "restore": {**main_res["restore"], **copy_rates(main_res["payload"], main_res["restore"]["mean_ms"])},
+            "dirty_blocks": len(case.dirty_ids), "payload_MB": main_res["payload"] / 1e6,
+        },
+        "paper_context": PAPER_CONTEXT,
+    }
+    cpu = None
+    if not args.only_timed:
+        import oracle
+        oracle.build()
+        cpu = cpu_baseline(case, oracle)
+        log(f"[bench] cpu baseline done: {cpu['value']:.3f} GB/s on {cpu['cores']} threads")
+    # free the timed workload before the large cases
+    for k in ("dec", "pool", "ids", "replica"):
+        main_res.pop(k)
+    torch.cuda.empty_cache()
+    if not args.only_timed:
+        extra["replication_mix"] = bench_replication_mix(args, kvflow, W)
+        log("[bench] replication_mix done")
+        torch.cuda.empty_cache()
+        extra["llama8b_layer"] = bench_llama_layer(args, kvflow, W)
+        log("[bench] llama8b_layer done")
+        torch.cuda.empty_cache()
+        extra["recovery"] = bench_recovery(args, kvflow, W, args.recovery_blocks)
+        log("[bench] recovery done")
+
+    line = {
+        "metric": "paged decode KV GB/s (pack/restore GB/s under extra), % of HBM peak, 1 MI355X",
+        "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "long_context: batch 8, 32 query heads, 8 KV heads, head_dim 128, block_size 16, "
+                               "context lengths uniform in [16384, 65536] (seed 2), pool 1.25x needed blocks with "
+                               "shuffled block tables; step = decode, pack 10% of in-use blocks, restore them",
+                   "kv_bytes_per_step": main_res["kv_bytes"], "pack_payload_bytes": main_res["payload"]},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "extra": extra,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
