@@ -66,8 +66,8 @@ class Decode:
         self.max_len = case.max_context_len
         nbytes = kvflow.kv_decode_workspace_bytes(case.batch, g.num_q_heads, g.num_kv_heads, g.head_dim,
                                                   self.max_len, 0)
-        self.ws = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device="cuda") if nbytes else None
-        self.partition = kvflow.kv_decode_partition_tokens(case.batch, g.num_kv_heads, self.max_len, 0)
+        self.ws = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")
+        self.workgroups = kvflow.kv_decode_workgroups(case.batch, g.num_kv_heads, self.max_len, 0)
         self.scale = float(g.scale)
 
     def run(self, stream=None):
@@ -222,7 +222,7 @@ def bench_recovery(args, kvflow, W, num_blocks):
         "restore": {**r, **copy_rates(payload, r["mean_ms"])},
         "pack": {**p, **copy_rates(payload, p["mean_ms"])},
         "pack_of_restore_is_identity": same,
-        "decode_after_restore": {**d, "kv_GB": rc.decode.kv_bytes / 1e9, "partition_tokens": dec.partition,
+        "decode_after_restore": {**d, "kv_GB": rc.decode.kv_bytes / 1e9, "workgroups": dec.workgroups,
                                  "kv_GBps": rc.decode.kv_bytes / (d["mean_ms"] * 1e-3) / 1e9,
                                  "frac_hbm_peak": rc.decode.kv_bytes / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
@@ -261,7 +261,7 @@ def bench_replication_mix(args, kvflow, W):
     kv = case.kv_bytes
     return {
         "kv_GB": kv / 1e9, "dirty_blocks": n, "pack_payload_MB": n * g.block_bytes / 1e6,
-        "partition_tokens": dec.partition,
+        "workgroups": dec.workgroups,
         "decode_alone": {**d, "kv_GBps": kv / (d["mean_ms"] * 1e-3) / 1e9,
                          "frac_hbm_peak": kv / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "pack_alone": {**p, **copy_rates(n * g.block_bytes, p["mean_ms"])},
@@ -276,7 +276,7 @@ def bench_llama_layer(args, kvflow, W):
     dec = Decode(case, pool, kvflow)
     d = time_calls(dec.run, 50, 10)
     kv = case.kv_bytes
-    return {"kv_GB": kv / 1e9, "partition_tokens": dec.partition, **d,
+    return {"kv_GB": kv / 1e9, "workgroups": dec.workgroups, **d,
             "kv_GBps": kv / (d["mean_ms"] * 1e-3) / 1e9,
             "note": "working set near the last-level cache size: latency figure, not an HBM measurement"}
 
@@ -317,7 +317,7 @@ def main():
     extra = {
         "timed_workload": {
             "decode": {**d, "kv_GBps": achieved, "frac_hbm_peak": achieved / HBM_PEAK_GBPS,
-                       "partition_tokens": main_res["dec"].partition},
+                       "workgroups": main_res["dec"].workgroups},
             "pack": {**main_res["pack"], **copy_rates(main_res["payload"], main_res["pack"]["mean_ms"])},
             "restore": {**main_res["restore"], **copy_rates(main_res["payload"], main_res["restore"]["mean_ms"])},
             "dirty_blocks": len(case.dirty_ids), "payload_MB": main_res["payload"] / 1e6,

@@ -67,21 +67,23 @@ typedef struct {
 size_t kv_block_bytes(const kv_pool_desc* pool);
 
 /*
- * Number of tokens of one sequence that a single workgroup reduces before the
- * partial results are merged (the split of long contexts across workgroups).
- * partition_tokens == 0 asks for the library's choice for this problem size;
- * the result is a multiple of 32.  Returns 0 on invalid arguments.
+ * Decode runs on a persistent grid: the cached tokens of the whole batch are cut into
+ * equally long runs, one per wavefront (4 wavefronts per workgroup), whatever the mix of context
+ * lengths.  num_workgroups == 0 asks for the library's choice (enough to fill the chip, fewer for
+ * small problems); a caller may pass a smaller positive number to leave compute units to other
+ * streams.  Returns the number of workgroups a call with these arguments launches, 0 on invalid
+ * arguments (non-positive sizes, num_workgroups < 0 or > 65535).
  */
-int32_t kv_decode_partition_tokens(int32_t batch, int32_t num_kv_heads, int32_t max_context_len,
-                                   int32_t partition_tokens);
+int32_t kv_decode_workgroups(int32_t batch, int32_t num_kv_heads, int32_t max_context_len,
+                             int32_t num_workgroups);
 
 /*
- * Bytes of workspace kv_decode_attn needs: 0 when every context fits one
- * partition, else batch * num_q_heads * splits * (head_dim + 2) * 4 with
- * splits = ceil(max_context_len / partition).  partition_tokens as above.
+ * Bytes of workspace kv_decode_attn needs for these arguments (always > 0 for valid arguments):
+ * the per-sequence tile counts plus one partial-result record per (run, KV-head row it touches,
+ * query head).  0 on invalid arguments.
  */
 size_t kv_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t num_kv_heads,
-                                 int32_t head_dim, int32_t max_context_len, int32_t partition_tokens);
+                                 int32_t head_dim, int32_t max_context_len, int32_t num_workgroups);
 
 /*
  * Paged decode attention (Sec. 3.2 item 3: attention state kept in a
@@ -97,25 +99,26 @@ size_t kv_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t num
  *   block_table    int32 [batch][max_blocks_per_seq], read; only the first
  *                  ceil(L/bs) entries of a row are dereferenced
  *   context_lens   int32 [batch], read
- *   max_context_len host-side upper bound of context_lens[]; sizes the grid and the split
- *   partition_tokens 0 = library's choice, else a multiple of 32 (see above)
- *   workspace      >= kv_decode_workspace_bytes(...) bytes, 16-byte aligned, scratch
- *                  (may be NULL when that size is 0)
+ *   max_context_len host-side upper bound of context_lens[]; sizes the grid and the workspace
+ *   num_workgroups 0 = library's choice, else the persistent grid size (see above)
+ *   workspace      >= kv_decode_workspace_bytes(...) bytes (same arguments), 16-byte aligned,
+ *                  scratch: contents on entry are ignored, contents on return are unspecified
  * Preconditions on device contents: 0 <= context_lens[b] <= max_context_len;
  * 0 <= block_table[b][j] < num_blocks for j < ceil(context_lens[b] / bs).
  * Slots past L in the last block, unreferenced table entries and unreferenced
  * blocks are never used and may hold anything, including NaN patterns.
- * The result depends only on logical token positions: two pools that hold the
- * same blocks under different physical ids give bitwise equal outputs.
+ * The result depends only on logical token positions: for the same batch, context
+ * lengths and num_workgroups, two pools that hold the same blocks under different
+ * physical ids give bitwise equal outputs.
  * Errors: NULL, SHAPE (dims <= 0, num_q_heads % num_kv_heads, num_q_heads /
- * num_kv_heads > 16, max_context_len > max_blocks_per_seq * bs, partition not a
- * multiple of 32), UNSUPPORTED (head_dim, block_size, dtypes), ALIGN, WORKSPACE,
- * LAUNCH.  batch == 0 returns KV_OK without a launch.
+ * num_kv_heads > 16, max_context_len > max_blocks_per_seq * bs, num_workgroups out of
+ * range), UNSUPPORTED (head_dim, block_size, dtypes), ALIGN, WORKSPACE, LAUNCH.
+ * batch == 0 returns KV_OK without a launch.
  */
 int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
                    const int32_t* block_table, int32_t max_blocks_per_seq,
                    const int32_t* context_lens, int32_t batch, int32_t num_q_heads,
-                   int32_t max_context_len, float scale, int32_t partition_tokens,
+                   int32_t max_context_len, float scale, int32_t num_workgroups,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*

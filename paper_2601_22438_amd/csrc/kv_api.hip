@@ -31,13 +31,31 @@ size_t block_bytes_of(const kv_pool_desc* pool)
     return (size_t)2 * pool->num_kv_heads * pool->block_size * pool->head_dim * 2;
 }
 
-int32_t resolve_partition(int32_t batch, int32_t num_kv_heads, int32_t max_context_len, int32_t requested)
+// Sequences per launch: bounded by the LDS scan and by 32-bit flat tile indices.
+int64_t slice_batch(int32_t num_kv_heads, int32_t max_context_len)
+{
+    const int64_t tiles_per_seq = ((int64_t)max_context_len + kTileTokens - 1) / kTileTokens;
+    const int64_t per_seq = (tiles_per_seq > 0 ? tiles_per_seq : 1) * num_kv_heads;
+    const int64_t fit = 0x7FFFFFFF / per_seq;
+    return fit < kDecodeMaxBatchPerLaunch ? fit : kDecodeMaxBatchPerLaunch;
+}
+
+// Persistent workgroups for one launch; 0 on invalid arguments.
+int32_t resolve_workgroups(int32_t batch, int32_t num_kv_heads, int32_t max_context_len, int32_t requested)
 {
     if (batch <= 0 || num_kv_heads <= 0 || max_context_len < 0 || requested < 0) return 0;
-    if (requested == 0) return choose_partition_tokens(batch, num_kv_heads, max_context_len);
-    if (requested % kTileTokens) return 0;
-    return requested;
+    if (requested > 0) return requested > 65535 ? 0 : requested;
+    int64_t bs = slice_batch(num_kv_heads, max_context_len);
+    if (bs < 1) return 0;
+    if (bs > batch) bs = batch;
+    const int64_t tiles = bs * num_kv_heads * (((int64_t)max_context_len + kTileTokens - 1) / kTileTokens);
+    int64_t wg = (tiles + kDecodeWaves * kDecodeMinTilesPerRun - 1) / (kDecodeWaves * kDecodeMinTilesPerRun);
+    if (wg < 1) wg = 1;
+    if (wg > kDecodeMaxWorkgroups) wg = kDecodeMaxWorkgroups;
+    return (int32_t)wg;
 }
+
+size_t cum_bytes(int64_t batch_slice) { return (size_t)(((batch_slice + 1) * 4 + 15) / 16 * 16); }
 
 int copy_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n,
                 bool to_replica, void* stream)
@@ -63,26 +81,29 @@ size_t kv_block_bytes(const kv_pool_desc* pool)
     return block_bytes_of(pool);
 }
 
-int32_t kv_decode_partition_tokens(int32_t batch, int32_t num_kv_heads, int32_t max_context_len,
-                                   int32_t partition_tokens)
+int32_t kv_decode_workgroups(int32_t batch, int32_t num_kv_heads, int32_t max_context_len,
+                             int32_t num_workgroups)
 {
-    return resolve_partition(batch, num_kv_heads, max_context_len, partition_tokens);
+    return resolve_workgroups(batch, num_kv_heads, max_context_len, num_workgroups);
 }
 
 size_t kv_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t num_kv_heads,
-                                 int32_t head_dim, int32_t max_context_len, int32_t partition_tokens)
+                                 int32_t head_dim, int32_t max_context_len, int32_t num_workgroups)
 {
-    const int32_t part = resolve_partition(batch, num_kv_heads, max_context_len, partition_tokens);
-    if (part == 0 || num_q_heads <= 0 || head_dim <= 0) return 0;
-    const int64_t splits = ((int64_t)max_context_len + part - 1) / part;
-    if (splits <= 1) return 0;
-    return (size_t)batch * num_q_heads * splits * (head_dim + 2) * sizeof(float);
+    const int32_t wg = resolve_workgroups(batch, num_kv_heads, max_context_len, num_workgroups);
+    if (wg == 0 || num_q_heads <= 0 || head_dim <= 0 || num_q_heads % num_kv_heads) return 0;
+    int64_t bs = slice_batch(num_kv_heads, max_context_len);
+    if (bs < 1) return 0;
+    if (bs > batch) bs = batch;
+    const int64_t slots = (int64_t)wg * kDecodeWaves + bs * num_kv_heads;
+    const int64_t group = num_q_heads / num_kv_heads;
+    return cum_bytes(bs) + (size_t)(slots * group * (head_dim + kRecordPad)) * sizeof(float);
 }
 
 int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
                    const int32_t* block_table, int32_t max_blocks_per_seq,
                    const int32_t* context_lens, int32_t batch, int32_t num_q_heads,
-                   int32_t max_context_len, float scale, int32_t partition_tokens,
+                   int32_t max_context_len, float scale, int32_t num_workgroups,
                    void* workspace, size_t workspace_bytes, void* stream)
 {
     int rc = check_pool(pool);
@@ -92,44 +113,46 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
     const int32_t group = num_q_heads / pool->num_kv_heads;
     if (group > kMaxGroup) return KV_ERR_SHAPE;
     if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * pool->block_size) return KV_ERR_SHAPE;
-    if (partition_tokens < 0 || partition_tokens % kTileTokens) return KV_ERR_SHAPE;
+    if (num_workgroups < 0 || num_workgroups > 65535) return KV_ERR_SHAPE;
+    if (num_q_heads > 65535) return KV_ERR_UNSUPPORTED;
     if (out_dtype != KV_DTYPE_BF16 && out_dtype != KV_DTYPE_F32) return KV_ERR_UNSUPPORTED;
-    if (batch > 65535) return KV_ERR_UNSUPPORTED;
     if (batch == 0) return KV_OK;
     if (!out || !q || !block_table || !context_lens) return KV_ERR_NULL;
     if (!aligned16(out) || !aligned16(q)) return KV_ERR_ALIGN;
-
-    const int32_t part = resolve_partition(batch, pool->num_kv_heads, max_context_len, partition_tokens);
-    int64_t splits = ((int64_t)max_context_len + part - 1) / part;
-    if (splits < 1) splits = 1;
-    if (splits > 0x7FFFFFFF / kTileTokens) return KV_ERR_SHAPE;
+    const int64_t slice = slice_batch(pool->num_kv_heads, max_context_len);
+    if (slice < 1) return KV_ERR_SHAPE;
+    const int32_t wg = resolve_workgroups(batch, pool->num_kv_heads, max_context_len, num_workgroups);
     const size_t need = kv_decode_workspace_bytes(batch, num_q_heads, pool->num_kv_heads, pool->head_dim,
-                                                  max_context_len, part);
-    if (need > 0) {
-        if (!workspace || workspace_bytes < need) return KV_ERR_WORKSPACE;
-        if (!aligned16(workspace)) return KV_ERR_ALIGN;
-    }
+                                                  max_context_len, num_workgroups);
+    if (!workspace || workspace_bytes < need) return KV_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return KV_ERR_ALIGN;
 
+    const int D = pool->head_dim;
+    const size_t out_elt = out_dtype == KV_DTYPE_F32 ? 4 : 2;
     DecodeParams p;
-    p.out = out;
-    p.q = (const uint16_t*)q;
     p.pool = (const uint16_t*)pool->base;
-    p.block_table = block_table;
-    p.context_lens = context_lens;
-    p.workspace = (float*)workspace;
     p.max_blocks_per_seq = max_blocks_per_seq;
-    p.batch = batch;
     p.num_q_heads = num_q_heads;
     p.num_kv_heads = pool->num_kv_heads;
     p.group = group;
     p.block_size = pool->block_size;
     p.block_shift = pool->block_size == 16 ? 4 : 5;
-    p.partition_tokens = part;
-    p.splits = (int32_t)splits;
     p.out_f32 = out_dtype == KV_DTYPE_F32;
     p.scale_log2e = (float)((double)scale * 1.4426950408889634074);
-    hipError_t e = launch_decode(p, pool->head_dim, (hipStream_t)stream);
-    return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
+    // Slices of the batch run back to back on the stream and reuse the workspace.
+    for (int64_t b0 = 0; b0 < batch; b0 += slice) {
+        const int64_t nb = batch - b0 < slice ? batch - b0 : slice;
+        p.out = (char*)out + (size_t)b0 * num_q_heads * D * out_elt;
+        p.q = (const uint16_t*)q + (size_t)b0 * num_q_heads * D;
+        p.block_table = block_table + (size_t)b0 * max_blocks_per_seq;
+        p.context_lens = context_lens + b0;
+        p.batch = (int32_t)nb;
+        p.ws_cum = (int32_t*)workspace;
+        p.ws_records = (float*)((char*)workspace + cum_bytes(slice < batch ? slice : batch));
+        hipError_t e = launch_decode(p, D, wg, (hipStream_t)stream);
+        if (e != hipSuccess) return KV_ERR_LAUNCH;
+    }
+    return KV_OK;
 }
 
 int kv_pack_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n, void* stream)

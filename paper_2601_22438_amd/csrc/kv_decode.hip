@@ -2,35 +2,37 @@
 // cached K/V, stored as fixed-size blocks reached through a block table (the block-represented
 // KV cache of paper Sec. 3.2 item 3).
 //
-// The work is a scan of the KV cache (HBM-bound).  A workgroup of 4 wavefronts owns one
-// (sequence, KV head, context partition); the G = Hq/Hkv query heads that share the KV head are
-// the 16-wide N side of MFMA tiles, so every K/V byte is loaded once and used by all G heads:
+// The work is one scan of the KV cache (HBM-bound), organised as a flat space of 32-token tiles:
+// tile index = ((sequence, KV head), tile within the sequence), sequences in batch order.  The
+// grid is persistent: every wavefront owns one contiguous, equally long run of that space, so the
+// load is even for any mix of context lengths, and a wavefront streams tile after tile with the
+// next tile's loads in flight.  Wavefronts never synchronise with each other after start-up.
+//
+// Per tile, the G = Hq/Hkv query heads that share the KV head form the 16-wide N side of MFMA
+// tiles, so each K/V byte is loaded once and serves all G heads:
 //     S^T[token][head] = K[token][d] * Q^T[d][head]          (v_mfma_f32_16x16x32_bf16, 16 tokens)
 //     O^T[d][head]    += V^T[d][token] * P^T[token][head]    (same instruction, 32 tokens)
-// With this orientation each lane's softmax statistics belong to one head (lane % 16), the
-// probabilities come out of the first product already in the register layout the second one
-// wants, and the running rescale of O is lane-local.
+// In this orientation a lane's softmax statistics belong to one head (lane % 16), the
+// probabilities leave the first product in the register layout the second one wants, and the
+// running rescale of O is lane-local.  K rows go from HBM straight into the A-operand layout;
+// V rows are loaded fully coalesced, staged in a per-wave LDS tile and read back transposed
+// (ds_read_b64_tr_b16).  Registers that an MFMA or the LDS write has consumed are refilled at
+// once with the next tile's loads.
 //
-// K rows go from HBM straight into the A-operand layout (lane = token row, 8 consecutive
-// channels).  V rows are loaded fully coalesced, staged in a per-wave LDS tile and read back
-// transposed (ds_read_b64_tr_b16) as the A operand of the second product.
-// Each wavefront runs an online softmax over its tiles (every 4th 32-token tile of the
-// partition) with the next tile's K/V loads in flight while the current tile is reduced; the
-// 4 wavefronts are merged through LDS, and partitions of one sequence by a second small kernel
-// in a fixed order, so the result depends only on logical token positions.
+// When a wavefront's run leaves a (sequence, KV head) row it writes one record (un-normalised
+// O, running max, denominator) per query head; a second small kernel merges the records of a
+// row in ascending run order.  Both the split and the merge order depend only on the context
+// lengths, so the result depends only on logical token positions.
 
 #include "kv_internal.h"
 
 namespace kvflow {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
 
 template <int D>
 struct Shape {
@@ -41,100 +43,160 @@ struct Shape {
     static constexpr int kVChunks = kTileTokens / kRowsPerChunk;   // 1 KiB loads per 32-token V tile
     static constexpr int kPitch = D * 2 + 32;        // LDS row pitch in bytes (pad avoids bank conflicts)
     static constexpr int kVTileBytes = kTileTokens * kPitch;
-    static constexpr int kMergeFloats = D + 2;       // workspace record per (head, partition): O[D], m, l
-    static constexpr int kLdsRow = D + 4;            // same record in LDS, padded to keep 16-byte alignment
-};
-
-template <int D>
-struct TileRegs {
-    bf16x8 k[2][Shape<D>::kSteps];
-    u32x4 v[Shape<D>::kVChunks];
+    static constexpr int kRecord = D + kRecordPad;   // floats per (run, row, head) record: O[D], m, l, pad
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// K/V bytes are used once per decode step: load them with the non-temporal hint so that they
+// stream through the caches instead of displacing each other.
+__device__ __forceinline__ u32x4 stream_load(const uint16_t* p)
+{
+    return __builtin_nontemporal_load((const u32x4*)p);
+}
+
+// First flat tile of run w when T tiles are dealt to W runs as evenly as possible.
+__device__ __forceinline__ int run_start(int w, int base, int rem) { return w * base + min(w, rem); }
+
+__device__ __forceinline__ int run_of_tile(int t, int base, int rem)
+{
+    const int big = rem * (base + 1);                // tiles held by the runs that got one extra
+    return t < big ? t / (base + 1) : rem + (t - big) / base;
+}
+
+// One flat tile: which sequence / KV head / tile, plus the physical blocks of its two subtiles.
+struct TileDesc {
+    int b, kvh, tile, L, ntiles;
+    int pb0, pb1;
+};
+
 template <int D>
-__global__ __launch_bounds__(kThreads) void decode_partition_kernel(const DecodeParams p)
+__global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const DecodeParams p)
 {
     using S = Shape<D>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, j = lane & 15;
+    const int B = p.batch, Hkv = p.num_kv_heads, G = p.group;
 
-    const int L = p.context_lens[b];
-    const int start = split * p.partition_tokens;
-    const int G = p.group;
-    const int64_t out_row0 = (int64_t)b * p.num_q_heads + (int64_t)kvh * G;
+    // ---- start-up: cum[b] = number of tiles of sequences before b (exclusive scan in LDS)
+    int* cum = (int*)smem;                                            // [B + 1]
+    {
+        __shared__ int wave_tot[kDecodeWaves];
+        const int per = (B + kDecodeThreads - 1) / kDecodeThreads;
+        const int lo = min(B, (int)threadIdx.x * per), hi = min(B, lo + per);
+        int mine = 0;
+        for (int b = lo; b < hi; ++b) mine += (p.context_lens[b] + kTileTokens - 1) / kTileTokens;
+        int incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(incl, off);
+            if (lane >= off) incl += t;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int before = incl - mine;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        for (int b = lo; b < hi; ++b) {
+            cum[b] = before;
+            before += (p.context_lens[b] + kTileTokens - 1) / kTileTokens;
+        }
+        if (threadIdx.x == kDecodeThreads - 1) cum[B] = before;       // its range ends at B
+        __syncthreads();
+        if (blockIdx.x == 0)                                          // the merge kernel reads this copy
+            for (int b = threadIdx.x; b <= B; b += kDecodeThreads) p.ws_cum[b] = cum[b];
+    }
+    const int T = Hkv * cum[B];
+    const int W = gridDim.x * kDecodeWaves;
+    const int base = T / W, rem = T % W;
+    const int w = blockIdx.x * kDecodeWaves + wave;
+    const int t_begin = run_start(w, base, rem), t_end = run_start(w + 1, base, rem);
 
-    if (start >= L) {
-        // Nothing cached in this partition.  An empty sequence still owes a row of zeros.
-        if (L == 0 && split == 0 && p.splits == 1) {
-            for (int e = threadIdx.x; e < G * D; e += kThreads) {
-                if (p.out_f32) ((float*)p.out)[out_row0 * D + e] = 0.f;
-                else ((uint16_t*)p.out)[out_row0 * D + e] = 0;
+    // ---- locate the first tile of this run: last b with Hkv * cum[b] <= t_begin
+    TileDesc cur = {0, 0, 0, 0, 0, 0, 0};
+    if (t_begin < t_end) {
+        int lo = 0, hi = B;                                           // Hkv*cum[lo] <= t_begin < Hkv*cum[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (Hkv * cum[mid] <= t_begin) lo = mid; else hi = mid;
+        }
+        cur.b = lo;
+        cur.ntiles = cum[lo + 1] - cum[lo];
+        const int r = t_begin - Hkv * cum[lo];
+        cur.kvh = r / cur.ntiles;
+        cur.tile = r % cur.ntiles;
+        cur.L = p.context_lens[lo];
+    }
+    __syncthreads();                                                  // cum[] is dead; LDS becomes V staging
+    if (t_begin >= t_end) return;
+
+    const int bs = p.block_size;
+    const int64_t head_elems = (int64_t)bs * D;                       // one (block, K|V, head) tile
+    const int64_t v_off = (int64_t)Hkv * head_elems;                  // K -> V within a block
+    const int64_t blk_elems = 2 * v_off;
+    const int koff = j * D + 8 * g;                                   // K operand: row j, channels 8g..
+    const int vrow = lane / S::kLanesPerRow;                          // V natural: row within a chunk
+    const int vcol = (lane % S::kLanesPerRow) * 8;
+    unsigned char* vt = smem + wave * S::kVTileBytes;                 // this wave's V staging tile
+    const int vw_off = vrow * S::kPitch + vcol * 2;
+    // transposed read: lanes 4e+c of a 16-lane group point at row 4g+e, channels 4c..4c+3 of a d-tile
+    const int vr_off = (4 * g + (j >> 2)) * S::kPitch + (j & 3) * 8;
+
+    auto fetch_ids = [&](TileDesc& d) {
+        const int32_t* row = p.block_table + (int64_t)d.b * p.max_blocks_per_seq;
+        const int t0 = d.tile * kTileTokens;
+        d.pb0 = row[t0 >> p.block_shift];
+        // a subtile with no valid token reuses subtile 0's block: its data is masked out below
+        d.pb1 = (t0 + 16 < d.L) ? row[(t0 + 16) >> p.block_shift] : d.pb0;
+    };
+    // step to the next flat tile; the caller guarantees that one exists
+    auto advance = [&](TileDesc& d) {
+        if (++d.tile == d.ntiles) {
+            d.tile = 0;
+            if (++d.kvh == Hkv) {
+                d.kvh = 0;
+                do { d.L = p.context_lens[++d.b]; } while (d.L == 0);
+                d.ntiles = (d.L + kTileTokens - 1) / kTileTokens;
             }
         }
-        return;
-    }
-    const int end = min(L, start + p.partition_tokens);
-    const int n_tiles = (end - start + kTileTokens - 1) / kTileTokens;
+    };
+    auto subtile_base = [&](const TileDesc& d, int u) -> int64_t {
+        const int t0 = d.tile * kTileTokens + 16 * u;
+        const bool live = u == 0 || t0 < d.L;
+        const int r0 = live ? (t0 & (bs - 1)) : ((t0 - 16) & (bs - 1));
+        return (int64_t)(u == 0 ? d.pb0 : d.pb1) * blk_elems + (int64_t)d.kvh * head_elems + (int64_t)r0 * D;
+    };
 
-    // ---- Q^T as the B operand: lane (g, j) holds head j, channels 32*ks + 8*g .. +7
-    bf16x8 qreg[S::kSteps];
-    {
-        const uint16_t* qrow = p.q + (out_row0 + j) * D + 8 * g;
+    bf16x8 qreg[S::kSteps];                                           // Q^T: head j, channels 32ks + 8g .. +7
+    bf16x8 kreg[2][S::kSteps];
+    u32x4 vreg[S::kVChunks];
+    auto load_q = [&](const TileDesc& d) {
+        const uint16_t* qrow = p.q + ((int64_t)d.b * p.num_q_heads + (int64_t)d.kvh * G + j) * D + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < S::kSteps; ++ks) {
             u32x4 t = {0u, 0u, 0u, 0u};
             if (j < G) t = *(const u32x4*)(qrow + 32 * ks);
             qreg[ks] = __builtin_bit_cast(bf16x8, t);
         }
-    }
-
-    const int32_t* table = p.block_table + (int64_t)b * p.max_blocks_per_seq;
-    const int bs = p.block_size;
-    const int64_t head_elems = (int64_t)bs * D;                       // one (block, K|V, head) tile
-    const int64_t v_off = (int64_t)p.num_kv_heads * head_elems;       // K -> V within a block
-    const int64_t blk_elems = 2 * v_off;
-    const int koff = j * D + 8 * g;                                   // K operand: row j, channels 8g..
-    const int vrow = lane / S::kLanesPerRow;                          // V natural: row within a chunk
-    const int vcol = (lane % S::kLanesPerRow) * 8;
-
-    unsigned char* vt = smem + wave * S::kVTileBytes;                 // this wave's V staging tile
-    const int vw_off = vrow * S::kPitch + vcol * 2;                   // ds_write position (+ chunk rows)
-    // transposed read: lanes 4e+c of a 16-lane group point at row 4g+e, channels 4c..4c+3 of a d-tile
-    const int vr_off = (4 * g + (j >> 2)) * S::kPitch + (j & 3) * 8;
-
-    // physical block of the 16-token subtile that starts at token t0 (t0 < end)
-    auto subtile_base = [&](int t0) -> int64_t {
-        const int blk = t0 >> p.block_shift;
-        const int r0 = t0 & (bs - 1);
-        const int64_t pb = table[blk];
-        return pb * blk_elems + (int64_t)kvh * head_elems + (int64_t)r0 * D;
     };
-
-    auto issue_loads = [&](TileRegs<D>& r, int tile) {
-        const int t0 = start + tile * kTileTokens;
-        const int64_t base0 = subtile_base(t0);
-        // a subtile with no valid token reuses subtile 0's address: its data is masked out below
-        const int64_t base1 = (t0 + 16 < end) ? subtile_base(t0 + 16) : base0;
-        const uint16_t* k0 = p.pool + base0 + koff;
-        const uint16_t* k1 = p.pool + base1 + koff;
+    auto issue_k = [&](const TileDesc& d) {
+        const uint16_t* k0 = p.pool + subtile_base(d, 0) + koff;
+        const uint16_t* k1 = p.pool + subtile_base(d, 1) + koff;
 #pragma unroll
         for (int ks = 0; ks < S::kSteps; ++ks) {
-            r.k[0][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(k0 + 32 * ks));
-            r.k[1][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(k1 + 32 * ks));
+            kreg[0][ks] = __builtin_bit_cast(bf16x8, stream_load(k0 + 32 * ks));
+            kreg[1][ks] = __builtin_bit_cast(bf16x8, stream_load(k1 + 32 * ks));
         }
-        const uint16_t* v0 = p.pool + base0 + v_off + vrow * D + vcol;
-        const uint16_t* v1 = p.pool + base1 + v_off + vrow * D + vcol;
+    };
+    auto issue_v = [&](const TileDesc& d) {
+        const uint16_t* v0 = p.pool + subtile_base(d, 0) + v_off + vrow * D + vcol;
+        const uint16_t* v1 = p.pool + subtile_base(d, 1) + v_off + vrow * D + vcol;
 #pragma unroll
         for (int c = 0; c < S::kVChunks; ++c) {
             const int row16 = (c * S::kRowsPerChunk) & 15;            // first row of the chunk in its subtile
-            const uint16_t* src = (c * S::kRowsPerChunk < 16 ? v0 : v1) + row16 * D;
-            r.v[c] = *(const u32x4*)src;
+            vreg[c] = stream_load((c * S::kRowsPerChunk < 16 ? v0 : v1) + row16 * D);
         }
     };
 
@@ -144,56 +206,77 @@ __global__ __launch_bounds__(kThreads) void decode_partition_kernel(const Decode
 #pragma unroll
     for (int dt = 0; dt < S::kDTiles; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto reduce_tile = [&](TileRegs<D>& r, int tile) {
-        const int tok0 = start + tile * kTileTokens;                  // first token of the tile
-        const bool ragged = tok0 + kTileTokens > end;                 // wave-uniform
+    fetch_ids(cur);
+    load_q(cur);
+    issue_k(cur);
+    issue_v(cur);
+    bool has_nxt = t_begin + 1 < t_end;
+    TileDesc nxt = cur;
+    if (has_nxt) { advance(nxt); fetch_ids(nxt); }
 
-        // ---- S^T = K Q^T for the two 16-token subtiles
+    for (int t = t_begin; t < t_end; ++t) {
+        // block ids are fetched two tiles ahead so that the table lookup is off the critical path
+        const bool has_nn = t + 2 < t_end;
+        TileDesc nn = nxt;
+        if (has_nn) { advance(nn); fetch_ids(nn); }
+        const bool row_ends = !has_nxt || nxt.b != cur.b || nxt.kvh != cur.kvh;
+        const int tok0 = cur.tile * kTileTokens;
+        const bool ragged = tok0 + kTileTokens > cur.L;               // wave-uniform
+
+        // ---- S^T = K Q^T for the two 16-token subtiles; then refill the K (and Q) registers
         f32x4 s[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             s[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < S::kSteps; ++ks)
-                s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.k[u][ks], qreg[ks], s[u], 0, 0, 0);
+                s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[u][ks], qreg[ks], s[u], 0, 0, 0);
         }
-        // lane (g, j): s[u][i] is head j, token tok0 + 16u + 4g + i
-        float t[8];
+        if (has_nxt) {
+            issue_k(nxt);
+            if (row_ends) load_q(nxt);
+        }
+
+        // ---- online softmax; lane (g, j): s[u][i] is head j, token tok0 + 16u + 4g + i
+        float tt[8];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) t[4 * u + i] = s[u][i] * p.scale_log2e;
+            for (int i = 0; i < 4; ++i) tt[4 * u + i] = s[u][i] * p.scale_log2e;
         if (ragged) {
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (tok0 + 16 * u + 4 * g + i >= end) t[4 * u + i] = -INFINITY;
+                    if (tok0 + 16 * u + 4 * g + i >= cur.L) tt[4 * u + i] = -INFINITY;
         }
-        float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+        float mx = fmaxf(fmaxf(fmaxf(tt[0], tt[1]), fmaxf(tt[2], tt[3])),
+                         fmaxf(fmaxf(tt[4], tt[5]), fmaxf(tt[6], tt[7])));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);                         // finite: the tile has a valid token
         const float alpha = fast_exp2(m_run - m_new);
         m_run = m_new;
-        float pr[8];
         float psum = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { pr[e] = fast_exp2(t[e] - m_new); psum += pr[e]; }
-        l_run = l_run * alpha + psum;
         bf16x8 pb;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)pr[e];
+        for (int e = 0; e < 8; ++e) {
+            const float pe = fast_exp2(tt[e] - m_new);
+            psum += pe;
+            pb[e] = (__bf16)pe;
+        }
+        l_run = l_run * alpha + psum;
 #pragma unroll
         for (int dt = 0; dt < S::kDTiles; ++dt) oacc[dt] *= alpha;
 
         // ---- V tile -> LDS (rows past the end are zeroed: 0 * NaN must not reach the sum)
 #pragma unroll
         for (int c = 0; c < S::kVChunks; ++c) {
-            u32x4 val = r.v[c];
-            if (ragged && tok0 + c * S::kRowsPerChunk + vrow >= end) val = u32x4{0u, 0u, 0u, 0u};
+            u32x4 val = vreg[c];
+            if (ragged && tok0 + c * S::kRowsPerChunk + vrow >= cur.L) val = u32x4{0u, 0u, 0u, 0u};
             *(u32x4*)(vt + vw_off + c * S::kRowsPerChunk * S::kPitch) = val;
         }
+        if (has_nxt) issue_v(nxt);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -202,137 +285,91 @@ __global__ __launch_bounds__(kThreads) void decode_partition_kernel(const Decode
 #pragma unroll
         for (int dt = 0; dt < S::kDTiles; ++dt) {
             typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vt + vr_off + dt * 32));
-            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vt + vr_off + 16 * S::kPitch + dt * 32));
-            typedef short s16x8 __attribute__((__vector_size__(16)));
-            s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vt + vr_off + dt * 32));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s16x4_ptr)(vt + vr_off + 16 * S::kPitch + dt * 32));
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pb, oacc[dt], 0, 0, 0);
         }
-        // the next tile's ds_write must not overtake these reads in program order
+        // the next tile's LDS writes must stay behind these reads in program order
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-    };
 
-    // ---- this wave's tiles: wave, wave + 4, ... ; loads run one tile ahead of the arithmetic
-    TileRegs<D> ra, rb;
-    int tile = wave;
-    if (tile < n_tiles) {
-        issue_loads(ra, tile);
-        while (true) {
-            if (tile + kWaves < n_tiles) issue_loads(rb, tile + kWaves);
-            reduce_tile(ra, tile);
-            tile += kWaves;
-            if (tile >= n_tiles) break;
-            if (tile + kWaves < n_tiles) issue_loads(ra, tile + kWaves);
-            reduce_tile(rb, tile);
-            tile += kWaves;
-            if (tile >= n_tiles) break;
-        }
-    }
-    // lanes of the same head hold disjoint token subsets under one shared max
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-
-    // ---- merge the 4 waves through LDS: per wave and head, O[D], m, l
-    __syncthreads();                                                  // V staging is dead from here on
-    float* mg = (float*)smem;
-    if (j < G) {
-        float* row = mg + (wave * kMaxGroup + j) * S::kLdsRow;
+        // ---- leaving the row: one record per query head, then start afresh
+        if (row_ends) {
+            float l_tot = l_run + __shfl_xor(l_run, 16);
+            l_tot += __shfl_xor(l_tot, 32);
+            if (j < G) {
+                const int64_t slot = (int64_t)w + (int64_t)cur.b * Hkv + cur.kvh;
+                float* rec = p.ws_records + (slot * G + j) * S::kRecord;
 #pragma unroll
-        for (int dt = 0; dt < S::kDTiles; ++dt)
-            *(f32x4*)(row + 16 * dt + 4 * g) = oacc[dt];              // channels 16dt + 4g .. +3
-        if (g == 0) { row[D] = m_run; row[D + 1] = l_run; }
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < G * D; e += kThreads) {
-        const int h = e / D, d = e % D;
-        float mw[kWaves];
-        float M = -INFINITY;
+                for (int dt = 0; dt < S::kDTiles; ++dt)
+                    *(f32x4*)(rec + 16 * dt + 4 * g) = oacc[dt];      // channels 16dt + 4g .. +3
+                if (g == 0) { rec[D] = m_run; rec[D + 1] = l_tot; }
+            }
+            m_run = -INFINITY;
+            l_run = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            mw[w] = mg[(w * kMaxGroup + h) * S::kLdsRow + D];
-            M = fmaxf(M, mw[w]);
+            for (int dt = 0; dt < S::kDTiles; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        float acc = 0.f, lsum = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float* row = mg + (w * kMaxGroup + h) * S::kLdsRow;
-            const float wgt = (mw[w] == -INFINITY) ? 0.f : fast_exp2(mw[w] - M);
-            acc += wgt * row[d];
-            lsum += wgt * row[D + 1];
-        }
-        if (p.splits == 1) {
-            const float o = acc / lsum;
-            if (p.out_f32) ((float*)p.out)[(out_row0 + h) * D + d] = o;
-            else ((__bf16*)p.out)[(out_row0 + h) * D + d] = (__bf16)o;
-        } else {
-            float* ws = p.workspace + ((out_row0 + h) * p.splits + split) * S::kMergeFloats;
-            ws[d] = acc;
-            if (d == 0) { ws[D] = M; ws[D + 1] = lsum; }
-        }
+        cur = nxt;
+        nxt = nn;
+        has_nxt = has_nn;
     }
 }
 
-// Combines the partitions of one (sequence, query head) in ascending partition order.
+// Combines the records of one (sequence, query head) in ascending run order and normalises.
 template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(const DecodeParams p)
+__global__ __launch_bounds__(D) void decode_merge_kernel(const DecodeParams p, int W)
 {
     using S = Shape<D>;
     const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-    const int64_t row = (int64_t)b * p.num_q_heads + h;
-    const int L = p.context_lens[b];
-    const int n = (L + p.partition_tokens - 1) / p.partition_tokens;
-    const float* ws = p.workspace + row * p.splits * S::kMergeFloats;
+    const int Hkv = p.num_kv_heads, G = p.group;
+    const int kvh = h / G, hg = h % G;
+    const int64_t out_idx = ((int64_t)b * p.num_q_heads + h) * D + d;
+    const int n = p.ws_cum[b + 1] - p.ws_cum[b];
     float o = 0.f;
     if (n > 0) {
+        const int T = Hkv * p.ws_cum[p.batch];
+        const int base = T / W, rem = T % W;
+        const int first = Hkv * p.ws_cum[b] + kvh * n;                // flat range of this row
+        const int w0 = run_of_tile(first, base, rem), w1 = run_of_tile(first + n - 1, base, rem);
+        const int64_t r = (int64_t)b * Hkv + kvh;
         float M = -INFINITY;
-        for (int s = 0; s < n; ++s) M = fmaxf(M, ws[s * S::kMergeFloats + D]);
+        for (int w = w0; w <= w1; ++w) M = fmaxf(M, p.ws_records[((w + r) * G + hg) * S::kRecord + D]);
         float acc = 0.f, lsum = 0.f;
-        for (int s = 0; s < n; ++s) {
-            const float wgt = fast_exp2(ws[s * S::kMergeFloats + D] - M);
-            acc += wgt * ws[s * S::kMergeFloats + d];
-            lsum += wgt * ws[s * S::kMergeFloats + D + 1];
+        for (int w = w0; w <= w1; ++w) {
+            const float* rec = p.ws_records + ((w + r) * G + hg) * S::kRecord;
+            const float wgt = fast_exp2(rec[D] - M);
+            acc += wgt * rec[d];
+            lsum += wgt * rec[D + 1];
         }
         o = acc / lsum;
     }
-    if (p.out_f32) ((float*)p.out)[row * D + d] = o;
-    else ((__bf16*)p.out)[row * D + d] = (__bf16)o;
-}
-
-int32_t choose_partition_tokens(int32_t batch, int32_t num_kv_heads, int32_t max_context_len)
-{
-    // Aim for a few workgroups per compute unit slot while keeping partitions long enough that
-    // the partial results (written and re-read once) stay a small fraction of the KV bytes.
-    const int64_t target_groups = 2048;
-    const int64_t pairs = (int64_t)batch * num_kv_heads;
-    int32_t part = 8192;
-    while (part > 256 && pairs * ((max_context_len + part - 1) / part) < target_groups) part >>= 1;
-    return part;
+    if (p.out_f32) ((float*)p.out)[out_idx] = o;
+    else ((__bf16*)p.out)[out_idx] = (__bf16)o;
 }
 
 template <int D>
-static hipError_t launch_decode_d(const DecodeParams& p, hipStream_t stream)
+static hipError_t launch_decode_d(const DecodeParams& p, int workgroups, hipStream_t stream)
 {
     using S = Shape<D>;
-    const size_t stage = (size_t)kWaves * S::kVTileBytes;
-    const size_t merge = (size_t)kWaves * kMaxGroup * S::kLdsRow * sizeof(float);
-    const size_t lds = stage > merge ? stage : merge;
-    dim3 grid((uint32_t)p.splits, (uint32_t)p.num_kv_heads, (uint32_t)p.batch);
-    hipLaunchKernelGGL(decode_partition_kernel<D>, grid, dim3(kThreads), lds, stream, p);
+    const size_t stage = (size_t)kDecodeWaves * S::kVTileBytes;
+    const size_t scan = (size_t)(p.batch + 1) * sizeof(int);
+    const size_t lds = stage > scan ? stage : scan;
+    hipLaunchKernelGGL(decode_partition_kernel<D>, dim3((uint32_t)workgroups), dim3(kDecodeThreads), lds,
+                       stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (p.splits > 1) {
-        dim3 mgrid((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1);
-        hipLaunchKernelGGL(decode_merge_kernel<D>, mgrid, dim3(D), 0, stream, p);
-        e = hipGetLastError();
-    }
-    return e;
+    hipLaunchKernelGGL(decode_merge_kernel<D>, dim3((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1), dim3(D),
+                       0, stream, p, workgroups * kDecodeWaves);
+    return hipGetLastError();
 }
 
-hipError_t launch_decode(const DecodeParams& p, int head_dim, hipStream_t stream)
+hipError_t launch_decode(const DecodeParams& p, int head_dim, int workgroups, hipStream_t stream)
 {
-    if (head_dim == 128) return launch_decode_d<128>(p, stream);
-    if (head_dim == 64) return launch_decode_d<64>(p, stream);
+    if (head_dim == 128) return launch_decode_d<128>(p, workgroups, stream);
+    if (head_dim == 64) return launch_decode_d<64>(p, workgroups, stream);
     return hipErrorInvalidValue;
 }
 

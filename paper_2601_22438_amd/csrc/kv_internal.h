@@ -7,8 +7,19 @@
 
 namespace kvflow {
 
-// Tokens one wavefront reduces per loop iteration; partitions are multiples of it.
+// Tokens one wavefront reduces per loop iteration.
 constexpr int kTileTokens = 32;
+// Decode workgroup: 4 independent wavefronts.
+constexpr int kDecodeWaves = 4;
+constexpr int kDecodeThreads = kDecodeWaves * 64;
+// Persistent decode grid that fills the chip: 256 compute units x 2 resident workgroups.
+constexpr int kDecodeMaxWorkgroups = 512;
+// A run shorter than this many tiles is not worth its record traffic: small problems get fewer runs.
+constexpr int kDecodeMinTilesPerRun = 4;
+// Sequences handled by one launch (their tile counts are scanned in LDS); larger batches are sliced.
+constexpr int kDecodeMaxBatchPerLaunch = 4096;
+// A record is O[head_dim], running max, denominator, padded to a multiple of 16 bytes.
+constexpr int kRecordPad = 4;
 // Largest query-head group (num_q_heads / num_kv_heads) the decode kernel handles: one MFMA tile.
 constexpr int kMaxGroup = 16;
 
@@ -18,19 +29,16 @@ struct DecodeParams {
     const uint16_t* pool;      // [NB][2][Hkv][bs][D] bf16
     const int32_t* block_table;
     const int32_t* context_lens;
-    float* workspace;          // [B][Hq][splits][D+2] fp32, used when splits > 1
+    int32_t* ws_cum;           // [batch + 1] tiles of the sequences before b (written by the kernel)
+    float* ws_records;         // [runs + batch*Hkv][group][D + kRecordPad] fp32
     int32_t max_blocks_per_seq;
     int32_t batch, num_q_heads, num_kv_heads, group;
     int32_t block_size, block_shift;
-    int32_t partition_tokens, splits;
     int32_t out_f32;
     float scale_log2e;         // scale * log2(e)
 };
 
-// Library's choice of partition size (tokens) for a problem; multiple of kTileTokens.
-int32_t choose_partition_tokens(int32_t batch, int32_t num_kv_heads, int32_t max_context_len);
-
-hipError_t launch_decode(const DecodeParams& p, int head_dim, hipStream_t stream);
+hipError_t launch_decode(const DecodeParams& p, int head_dim, int workgroups, hipStream_t stream);
 
 // dst/src are the replica and the pool; to_replica selects the direction.
 hipError_t launch_copy_blocks(void* replica, void* pool, size_t block_bytes, const int32_t* block_ids,

@@ -3,7 +3,7 @@
 Every function has the name and argument order of the C entry point it calls
 (see include/kvflow.h).  Tensors are torch CUDA tensors used as device memory;
 their ``data_ptr()`` and the current HIP stream handle are passed through.  There
-is no fallback: if the library cannot be loaded the import of any function fails.
+is no fallback: if the library is missing or cannot be loaded, every call raises.
 """
 from __future__ import annotations
 
@@ -46,8 +46,8 @@ def load() -> ctypes.CDLL:
     P, I32, I64, SZ, F = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
     PD = ctypes.POINTER(kv_pool_desc)
     lib.kv_block_bytes.restype, lib.kv_block_bytes.argtypes = SZ, [PD]
-    lib.kv_decode_partition_tokens.restype = I32
-    lib.kv_decode_partition_tokens.argtypes = [I32, I32, I32, I32]
+    lib.kv_decode_workgroups.restype = I32
+    lib.kv_decode_workgroups.argtypes = [I32, I32, I32, I32]
     lib.kv_decode_workspace_bytes.restype = SZ
     lib.kv_decode_workspace_bytes.argtypes = [I32, I32, I32, I32, I32, I32]
     lib.kv_decode_attn.restype = ctypes.c_int
@@ -98,18 +98,18 @@ def kv_block_bytes(pool: torch.Tensor) -> int:
     return int(load().kv_block_bytes(ctypes.byref(pool_desc(pool))))
 
 
-def kv_decode_partition_tokens(batch, num_kv_heads, max_context_len, partition_tokens=0) -> int:
-    return int(load().kv_decode_partition_tokens(batch, num_kv_heads, max_context_len, partition_tokens))
+def kv_decode_workgroups(batch, num_kv_heads, max_context_len, num_workgroups=0) -> int:
+    return int(load().kv_decode_workgroups(batch, num_kv_heads, max_context_len, num_workgroups))
 
 
 def kv_decode_workspace_bytes(batch, num_q_heads, num_kv_heads, head_dim, max_context_len,
-                              partition_tokens=0) -> int:
+                              num_workgroups=0) -> int:
     return int(load().kv_decode_workspace_bytes(batch, num_q_heads, num_kv_heads, head_dim,
-                                                max_context_len, partition_tokens))
+                                                max_context_len, num_workgroups))
 
 
 def kv_decode_attn(out, q, pool, block_table, context_lens, max_context_len, scale,
-                   partition_tokens=0, workspace=None, stream=None) -> None:
+                   num_workgroups=0, workspace=None, stream=None) -> None:
     """Enqueue paged decode attention; ``out`` ([B][Hq][D], bf16 or fp32) is written in place."""
     batch, num_q_heads, _ = q.shape
     out_dtype = {torch.bfloat16: KV_DTYPE_BF16, torch.float32: KV_DTYPE_F32}[out.dtype]
@@ -117,7 +117,7 @@ def kv_decode_attn(out, q, pool, block_table, context_lens, max_context_len, sca
     _check(load().kv_decode_attn(
         _ptr(out), out_dtype, _ptr(q), ctypes.byref(pool_desc(pool)), _ptr(block_table),
         block_table.shape[1], _ptr(context_lens), batch, num_q_heads, int(max_context_len),
-        float(scale), int(partition_tokens), _ptr(workspace), ws_bytes, _stream_handle(stream)))
+        float(scale), int(num_workgroups), _ptr(workspace), ws_bytes, _stream_handle(stream)))
 
 
 def kv_pack_blocks(replica, pool, block_ids, n=None, stream=None) -> None:

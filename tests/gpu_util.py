@@ -30,16 +30,18 @@ class DeviceCase:
         self.max_len = case.max_context_len
         self.scale = float(g.scale)
 
-    def decode(self, out_dtype=torch.float32, partition_tokens=0, max_len=None, block_table=None, pool=None):
+    def decode(self, out_dtype=torch.float32, workgroups=0, max_len=None, block_table=None, pool=None):
         c, g = self.case, self.case.geom
         max_len = self.max_len if max_len is None else max_len
         out = torch.full((c.batch, g.num_q_heads, g.head_dim), float("nan"), dtype=out_dtype, device="cuda")
         nbytes = kvflow.kv_decode_workspace_bytes(c.batch, g.num_q_heads, g.num_kv_heads, g.head_dim,
-                                                  max_len, partition_tokens)
-        ws = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device="cuda") if nbytes else None
+                                                  max_len, workgroups)
+        assert nbytes > 0
+        # workspace contents on entry must not matter: fill it with NaN
+        ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
         kvflow.kv_decode_attn(out, self.q, self.pool if pool is None else pool,
                               self.block_table if block_table is None else block_table,
-                              self.context_lens, max_len, self.scale, partition_tokens, ws)
+                              self.context_lens, max_len, self.scale, workgroups, ws)
         torch.cuda.synchronize()
         return out
 

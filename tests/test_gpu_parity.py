@@ -99,23 +99,23 @@ RAGGED = [1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 127, 128, 129, 2
 
 
 @pytest.mark.parametrize("geom", GEOMS)
-@pytest.mark.parametrize("part", [0, 32, 64, 128])
-def test_decode_ragged_lengths_and_partitions(oracle, geom, part):
+@pytest.mark.parametrize("wgs", [0, 1, 3, 64])
+def test_decode_ragged_lengths_and_grid_sizes(oracle, geom, wgs):
     Hq, Hkv, D, bs = geom
     case = make(107, Hq, Hkv, D, bs, RAGGED, MB=-(-300 // bs))
     want = oracle_decode(oracle, case)
     dc = DeviceCase(case)
     for dt in (torch.float32, torch.bfloat16):
-        assert_close_to_oracle(dc.decode(dt, partition_tokens=part), want, f"{geom} part={part} {dt}")
+        assert_close_to_oracle(dc.decode(dt, workgroups=wgs), want, f"{geom} workgroups={wgs} {dt}")
 
 
 def test_decode_zero_length_sequences(oracle):
     case = make(109, 8, 2, 64, 16, [0, 50, 0, 17], MB=8)
     want = oracle_decode(oracle, case)
     dc = DeviceCase(case)
-    for part in (0, 32):
-        got = dc.decode(torch.float32, partition_tokens=part)
-        assert_close_to_oracle(got, want, f"zero-length part={part}")
+    for wgs in (0, 2):
+        got = dc.decode(torch.float32, workgroups=wgs)
+        assert_close_to_oracle(got, want, f"zero-length workgroups={wgs}")
         assert torch.count_nonzero(got[0]) == 0 and torch.count_nonzero(got[2]) == 0
 
 
@@ -147,8 +147,8 @@ def test_decode_ignores_poisoned_tail_slots_unused_blocks_and_table_entries(orac
             pid = case.block_table[b, jb]
             pool[pid, :, :, :valid] = case.pool[pid, :, :, :valid]
     dc = DeviceCase(case, pool_bits=pool)
-    for part in (0, 64):
-        got = dc.decode(torch.float32, partition_tokens=part)
+    for wgs in (0, 5):
+        got = dc.decode(torch.float32, workgroups=wgs)
         assert_close_to_oracle(got, want, "poisoned")
     # a looser host bound on the context length must not change anything either
     got2 = dc.decode(torch.float32, max_len=12 * 16)
@@ -162,9 +162,9 @@ def test_decode_bitwise_invariant_under_block_permutation(oracle):
     pool2 = np.empty_like(case.pool)
     pool2[perm] = case.pool
     table2 = np.where(case.block_table >= 0, perm[np.maximum(case.block_table, 0)], -1).astype(np.int32)
-    for part in (0, 128):
-        a = dc.decode(torch.float32, partition_tokens=part)
-        b = dc.decode(torch.float32, partition_tokens=part, pool=bf16_tensor(pool2),
+    for wgs in (0, 7):
+        a = dc.decode(torch.float32, workgroups=wgs)
+        b = dc.decode(torch.float32, workgroups=wgs, pool=bf16_tensor(pool2),
                       block_table=torch.from_numpy(table2).cuda())
         assert torch.equal(a, b)
 
