@@ -318,36 +318,90 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
     }
 }
 
-// Combines the records of one (sequence, query head) in ascending run order and normalises.
+// Combines the records of one (sequence, query head) in a fixed order and normalises.
+// The kernel is latency-bound (cold reads of a few KB per workgroup), so every load of a pass is
+// issued before the first use: the 256 threads are kSlices groups of D/4 lanes, a lane owns 4
+// channels, group s takes runs s, s + kSlices, ... of the pass, and the running max and
+// denominators of the pass go through LDS.  Partial sums of the groups are added in group order.
+constexpr int kMergeThreads = 256;
+constexpr int kMergePer = 8;                         // records per thread and pass
+
 template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(const DecodeParams p, int W)
+__global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const DecodeParams p, int W)
 {
     using S = Shape<D>;
-    const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+    constexpr int kLanes = D / 4;
+    constexpr int kSlices = kMergeThreads / kLanes;
+    constexpr int kChunk = kSlices * kMergePer;                       // runs per pass (<= 128)
+    __shared__ float sm[kChunk], sl[kChunk];
+    __shared__ __attribute__((aligned(16))) float red[kSlices * D];
+    __shared__ float redl[kSlices];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int Hkv = p.num_kv_heads, G = p.group;
     const int kvh = h / G, hg = h % G;
-    const int64_t out_idx = ((int64_t)b * p.num_q_heads + h) * D + d;
+    const int slice = tid / kLanes, c = tid % kLanes;
+    const int64_t out0 = ((int64_t)b * p.num_q_heads + h) * D;
     const int n = p.ws_cum[b + 1] - p.ws_cum[b];
-    float o = 0.f;
-    if (n > 0) {
-        const int T = Hkv * p.ws_cum[p.batch];
-        const int base = T / W, rem = T % W;
-        const int first = Hkv * p.ws_cum[b] + kvh * n;                // flat range of this row
-        const int w0 = run_of_tile(first, base, rem), w1 = run_of_tile(first + n - 1, base, rem);
-        const int64_t r = (int64_t)b * Hkv + kvh;
-        float M = -INFINITY;
-        for (int w = w0; w <= w1; ++w) M = fmaxf(M, p.ws_records[((w + r) * G + hg) * S::kRecord + D]);
-        float acc = 0.f, lsum = 0.f;
-        for (int w = w0; w <= w1; ++w) {
-            const float* rec = p.ws_records + ((w + r) * G + hg) * S::kRecord;
-            const float wgt = fast_exp2(rec[D] - M);
-            acc += wgt * rec[d];
-            lsum += wgt * rec[D + 1];
+    if (n == 0) {                                                     // empty sequence: a row of zeros
+        if (tid < D) {
+            if (p.out_f32) ((float*)p.out)[out0 + tid] = 0.f;
+            else ((uint16_t*)p.out)[out0 + tid] = 0;
         }
-        o = acc / lsum;
+        return;
     }
-    if (p.out_f32) ((float*)p.out)[out_idx] = o;
-    else ((__bf16*)p.out)[out_idx] = (__bf16)o;
+    const int T = Hkv * p.ws_cum[p.batch];
+    const int base = T / W, rem = T % W;
+    const int first = Hkv * p.ws_cum[b] + kvh * n;                    // flat range of this row
+    const int w0 = run_of_tile(first, base, rem), w1 = run_of_tile(first + n - 1, base, rem);
+    const int nr = w1 - w0 + 1;
+    const int64_t rec_stride = (int64_t)G * S::kRecord;               // run w -> run w + 1, same row and head
+    const float* recs = p.ws_records + ((w0 + (int64_t)b * Hkv + kvh) * G + hg) * S::kRecord;
+
+    float M = -INFINITY, lsum = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < nr; c0 += kChunk) {
+        const int cn = min(kChunk, nr - c0);
+        f32x4 vals[kMergePer];
+#pragma unroll
+        for (int k = 0; k < kMergePer; ++k) {
+            const int i = k * kSlices + slice;
+            vals[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (i < cn) vals[k] = *(const f32x4*)(recs + (c0 + i) * rec_stride + 4 * c);
+        }
+        if (tid < cn) {
+            sm[tid] = recs[(c0 + tid) * rec_stride + D];
+            sl[tid] = recs[(c0 + tid) * rec_stride + D + 1];
+        }
+        __syncthreads();
+        float cm = -INFINITY;
+        for (int i = 0; i < cn; ++i) cm = fmaxf(cm, sm[i]);
+        const float Mn = fmaxf(M, cm);
+        const float a = fast_exp2(M - Mn);
+        M = Mn;
+        acc *= a;
+        lsum *= a;
+#pragma unroll
+        for (int k = 0; k < kMergePer; ++k) {
+            const int i = k * kSlices + slice;
+            if (i < cn) {
+                const float wgt = fast_exp2(sm[i] - Mn);
+                acc += wgt * vals[k];
+                lsum += wgt * sl[i];
+            }
+        }
+        __syncthreads();
+    }
+    *(f32x4*)(red + slice * D + 4 * c) = acc;
+    if (c == 0) redl[slice] = lsum;
+    __syncthreads();
+    if (tid < D) {
+        float o = 0.f, l = 0.f;
+#pragma unroll
+        for (int sidx = 0; sidx < kSlices; ++sidx) { o += red[sidx * D + tid]; l += redl[sidx]; }
+        o /= l;
+        if (p.out_f32) ((float*)p.out)[out0 + tid] = o;
+        else ((__bf16*)p.out)[out0 + tid] = (__bf16)o;
+    }
 }
 
 template <int D>
@@ -361,8 +415,8 @@ static hipError_t launch_decode_d(const DecodeParams& p, int workgroups, hipStre
                        stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_merge_kernel<D>, dim3((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1), dim3(D),
-                       0, stream, p, workgroups * kDecodeWaves);
+    hipLaunchKernelGGL(decode_merge_kernel<D>, dim3((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1),
+                       dim3(kMergeThreads), 0, stream, p, workgroups * kDecodeWaves);
     return hipGetLastError();
 }
 
