@@ -1,0 +1,119 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, and rejects bad arguments before any launch (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvflow.h")
+LIB = os.path.join(ROOT, "paper_2601_22438_amd", "libkvflow.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2601_22438_amd.build import build_library
+        build_library()
+    from paper_2601_22438_amd import kvflow
+    return kvflow.load()
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_entry_points():
+    names = declared_functions()
+    for must in ("kv_decode_attn", "kv_pack_blocks", "kv_restore_blocks"):
+        assert must in names
+
+
+def test_library_exports_every_declared_function(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_binding_has_the_same_names():
+    from paper_2601_22438_amd import kvflow
+    for name in declared_functions():
+        assert hasattr(kvflow, name), name
+
+
+def desc(kvflow, base=0x10000, nb=8, hkv=2, bs=16, d=64, dtype=0):
+    return kvflow.kv_pool_desc(base, nb, hkv, bs, d, dtype)
+
+
+def decode(lib, kvflow, pool, out=0x20000, q=0x30000, table=0x40000, lens=0x50000, mb=4, batch=2, hq=8,
+           max_len=64, wgs=0, ws=0x60000, ws_bytes=1 << 30, out_dtype=1):
+    return lib.kv_decode_attn(out, out_dtype, q, ctypes.byref(pool), table, mb, lens, batch, hq, max_len,
+                              0.125, wgs, ws, ws_bytes, None)
+
+
+def test_decode_rejects_bad_arguments_before_any_launch(lib):
+    from paper_2601_22438_amd import kvflow
+    ok = desc(kvflow)
+    assert decode(lib, kvflow, desc(kvflow, base=0)) == -1                       # NULL pool
+    assert decode(lib, kvflow, ok, out=0) == -1
+    assert decode(lib, kvflow, ok, q=0) == -1
+    assert decode(lib, kvflow, ok, table=0) == -1
+    assert decode(lib, kvflow, ok, lens=0) == -1
+    assert decode(lib, kvflow, desc(kvflow, nb=0)) == -2
+    assert decode(lib, kvflow, ok, hq=7) == -2                                   # not a multiple of Hkv
+    assert decode(lib, kvflow, ok, hq=2 * 17) == -2                              # group > 16
+    assert decode(lib, kvflow, ok, max_len=65) == -2                             # beyond the table row
+    assert decode(lib, kvflow, ok, wgs=-1) == -2
+    assert decode(lib, kvflow, desc(kvflow, d=96)) == -3
+    assert decode(lib, kvflow, desc(kvflow, bs=8)) == -3
+    assert decode(lib, kvflow, desc(kvflow, dtype=1)) == -3
+    assert decode(lib, kvflow, ok, out_dtype=2) == -3
+    assert decode(lib, kvflow, desc(kvflow, base=0x10008)) == -4
+    assert decode(lib, kvflow, ok, out=0x20004) == -4
+    assert decode(lib, kvflow, ok, ws=0x60004) == -4
+    assert decode(lib, kvflow, ok, ws=0) == -5
+    assert decode(lib, kvflow, ok, ws_bytes=16) == -5
+    assert decode(lib, kvflow, ok, batch=0) == 0                                 # nothing to do
+    assert decode(lib, kvflow, ok, batch=-1) == -2
+
+
+def test_pack_restore_reject_bad_arguments_before_any_launch(lib):
+    from paper_2601_22438_amd import kvflow
+    ok = desc(kvflow)
+    for fn, args in ((lib.kv_pack_blocks, lambda p, rep, ids, n: (rep, ctypes.byref(p), ids, n, None)),
+                     (lib.kv_restore_blocks, lambda p, rep, ids, n: (ctypes.byref(p), rep, ids, n, None))):
+        assert fn(*args(ok, 0x20000, 0x30000, 0)) == 0                           # empty list
+        assert fn(*args(ok, 0, 0x30000, 3)) == -1
+        assert fn(*args(ok, 0x20000, 0, 3)) == -1
+        assert fn(*args(desc(kvflow, base=0), 0x20000, 0x30000, 3)) == -1
+        assert fn(*args(ok, 0x20000, 0x30000, -1)) == -2
+        assert fn(*args(desc(kvflow, hkv=0), 0x20000, 0x30000, 3)) == -2
+        assert fn(*args(desc(kvflow, d=100), 0x20000, 0x30000, 3)) == -3
+        assert fn(*args(ok, 0x20008, 0x30000, 3)) == -4
+
+
+def test_block_bytes_workgroups_and_workspace_size(lib):
+    from paper_2601_22438_amd import kvflow
+    assert lib.kv_block_bytes(ctypes.byref(desc(kvflow, hkv=8, bs=16, d=128))) == 65536
+    assert lib.kv_block_bytes(ctypes.byref(desc(kvflow, hkv=2, bs=16, d=64))) == 8192
+    assert lib.kv_block_bytes(None) == 0
+    # small problems get fewer workgroups, big ones the full persistent grid; a request is honoured
+    assert kvflow.kv_decode_workgroups(4, 2, 256) == 4
+    assert kvflow.kv_decode_workgroups(8, 8, 65536) == 512
+    assert kvflow.kv_decode_workgroups(8, 8, 65536, 100) == 100
+    assert kvflow.kv_decode_workgroups(0, 8, 65536) == 0
+    assert kvflow.kv_decode_workgroups(8, 8, 65536, -3) == 0
+    # workspace = tile counts (16-byte padded) + (runs + rows) * group * (D + 4) floats
+    wgs = 512
+    want = 48 + (wgs * 4 + 8 * 8) * 4 * (128 + 4) * 4      # 9 counts = 36 bytes, padded to 48
+    assert kvflow.kv_decode_workspace_bytes(8, 32, 8, 128, 65536) == want
+    assert kvflow.kv_decode_workspace_bytes(8, 33, 8, 128, 65536) == 0
+
+
+def test_status_strings(lib):
+    from paper_2601_22438_amd import kvflow
+    assert kvflow.kv_status_string(0) == "ok"
+    texts = {kvflow.kv_status_string(s) for s in range(-7, 1)}
+    assert len(texts) == 8 and "unknown status" not in texts
+    assert kvflow.kv_status_string(-99) == "unknown status"
