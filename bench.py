@@ -29,7 +29,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM traffic per decode launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
 # WRITE_SIZE), scaled by the same counters on a plain copy of known size; see profiles/.  Valid
 # only for the kernel source the counters were taken with.
-DECODE_TRAFFIC = {"kernel_sha256": None, "fetch_bytes": None, "write_bytes": None}
+DECODE_TRAFFIC = {"kernel_sha256": "a61dcb77619b1d7cb589feb7651dab4efa8c9ab5058169b19582d8fea1727bd9",
+                  "fetch_bytes": 1294375787, "write_bytes": 4525093}
 
 PAPER_CONTEXT = {
     "note": "end-to-end serving figures from the paper, other hardware, context only",
@@ -161,9 +162,10 @@ def bench_long_context(args, kvflow, W):
     return res
 
 
-def cpu_baseline(case, oracle, n_seqs=2):
+def cpu_baseline(case, oracle, n_seqs=None):
     """The oracle as it stands, timed on this host: all query heads of the first n_seqs sequences."""
     g = case.geom
+    n_seqs = case.batch if n_seqs is None else n_seqs
     rows = np.array([(b, h) for b in range(n_seqs) for h in range(g.num_q_heads)], np.int32)
     t0 = time.perf_counter()
     _, threads = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale,
@@ -289,6 +291,9 @@ def main():
     ap.add_argument("--copy-iters", type=int, default=5)
     ap.add_argument("--recovery-blocks", type=int, default=200_000)
     ap.add_argument("--only-timed", action="store_true", help="skip the extra cases and the CPU baseline")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after timing, run one plain device copy of the pool (known size) so that a "
+                         "counter-collecting profiler run has a yardstick for FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: this data path uses no second GPU; run with --gpus 1")
@@ -330,6 +335,13 @@ def main():
         oracle.build()
         cpu = cpu_baseline(case, oracle)
         log(f"[bench] cpu baseline done: {cpu['value']:.3f} GB/s on {cpu['cores']} threads")
+    if args.calibration_copy:
+        src_pool = main_res["pool"]
+        dst_pool = torch.empty_like(src_pool)
+        dst_pool.copy_(src_pool)
+        torch.cuda.synchronize()
+        extra["calibration_copy_bytes"] = src_pool.numel() * 2
+        del dst_pool
     # free the timed workload before the large cases
     for k in ("dec", "pool", "ids", "replica"):
         main_res.pop(k)
