@@ -26,6 +26,8 @@
 
 #include "kv_internal.h"
 
+#include <type_traits>
+
 namespace kvflow {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -55,6 +57,12 @@ __device__ __forceinline__ u32x4 stream_load(const uint16_t* p)
     return __builtin_nontemporal_load((const u32x4*)p);
 }
 
+// The running max of a head only has to be an upper bound of the scores up to a bounded slack
+// (softmax is invariant under the reference point): it is raised, with the cross-lane reduction
+// and the rescale of O that go with it, only when some score of the tile exceeds it by more than
+// this many binary orders of magnitude.  Probabilities then stay below 2^kMaxSlack.
+constexpr float kMaxSlack = 8.f;
+
 // First flat tile of run w when T tiles are dealt to W runs as evenly as possible.
 __device__ __forceinline__ int run_start(int w, int base, int rem) { return w * base + min(w, rem); }
 
@@ -70,8 +78,16 @@ struct TileDesc {
     int pb0, pb1;
 };
 
+// The pointers are separate __restrict__ kernel arguments (not members of the by-value struct) so
+// that the compiler may read the block table and the context lengths with scalar loads, which
+// do not share a counter with the K/V vector loads in flight.
+// The register budget is capped at that of 3 waves per SIMD: the accumulators then stay in
+// ordinary vector registers (no copies to and from the accumulation file around the rescale).
 template <int D>
-__global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const DecodeParams p)
+__global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void decode_partition_kernel(
+    const DecodeParams p, const uint16_t* __restrict__ q_ptr, const uint16_t* __restrict__ pool_ptr,
+    const int32_t* __restrict__ table_ptr, const int32_t* __restrict__ lens_ptr,
+    int32_t* __restrict__ ws_cum, float* __restrict__ ws_records)
 {
     using S = Shape<D>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -88,7 +104,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
         const int per = (B + kDecodeThreads - 1) / kDecodeThreads;
         const int lo = min(B, (int)threadIdx.x * per), hi = min(B, lo + per);
         int mine = 0;
-        for (int b = lo; b < hi; ++b) mine += (p.context_lens[b] + kTileTokens - 1) / kTileTokens;
+        for (int b = lo; b < hi; ++b) mine += (lens_ptr[b] + kTileTokens - 1) / kTileTokens;
         int incl = mine;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -101,12 +117,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
         for (int w = 0; w < wave; ++w) before += wave_tot[w];
         for (int b = lo; b < hi; ++b) {
             cum[b] = before;
-            before += (p.context_lens[b] + kTileTokens - 1) / kTileTokens;
+            before += (lens_ptr[b] + kTileTokens - 1) / kTileTokens;
         }
         if (threadIdx.x == kDecodeThreads - 1) cum[B] = before;       // its range ends at B
         __syncthreads();
         if (blockIdx.x == 0)                                          // the merge kernel reads this copy
-            for (int b = threadIdx.x; b <= B; b += kDecodeThreads) p.ws_cum[b] = cum[b];
+            for (int b = threadIdx.x; b <= B; b += kDecodeThreads) ws_cum[b] = cum[b];
     }
     const int T = Hkv * cum[B];
     const int W = gridDim.x * kDecodeWaves;
@@ -127,7 +143,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
         const int r = t_begin - Hkv * cum[lo];
         cur.kvh = r / cur.ntiles;
         cur.tile = r % cur.ntiles;
-        cur.L = p.context_lens[lo];
+        cur.L = lens_ptr[lo];
     }
     __syncthreads();                                                  // cum[] is dead; LDS becomes V staging
     if (t_begin >= t_end) return;
@@ -145,11 +161,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
     const int vr_off = (4 * g + (j >> 2)) * S::kPitch + (j & 3) * 8;
 
     auto fetch_ids = [&](TileDesc& d) {
-        const int32_t* row = p.block_table + (int64_t)d.b * p.max_blocks_per_seq;
+        const int32_t* row = table_ptr + (int64_t)d.b * p.max_blocks_per_seq;
         const int t0 = d.tile * kTileTokens;
         d.pb0 = row[t0 >> p.block_shift];
-        // a subtile with no valid token reuses subtile 0's block: its data is masked out below
-        d.pb1 = (t0 + 16 < d.L) ? row[(t0 + 16) >> p.block_shift] : d.pb0;
+        // second subtile: if it has no valid token the index falls back to the block of the last
+        // token, which is subtile 0's block; its data is masked out below.  Two independent loads.
+        d.pb1 = row[min(t0 + 16, d.L - 1) >> p.block_shift];
     };
     // step to the next flat tile; the caller guarantees that one exists
     auto advance = [&](TileDesc& d) {
@@ -157,7 +174,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
             d.tile = 0;
             if (++d.kvh == Hkv) {
                 d.kvh = 0;
-                do { d.L = p.context_lens[++d.b]; } while (d.L == 0);
+                do { d.L = lens_ptr[++d.b]; } while (d.L == 0);
                 d.ntiles = (d.L + kTileTokens - 1) / kTileTokens;
             }
         }
@@ -170,29 +187,30 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
     };
 
     bf16x8 qreg[S::kSteps];                                           // Q^T: head j, channels 32ks + 8g .. +7
+    bf16x8 qnext[S::kSteps];                                          // same for the row that follows
     bf16x8 kreg[2][S::kSteps];
     u32x4 vreg[S::kVChunks];
-    auto load_q = [&](const TileDesc& d) {
-        const uint16_t* qrow = p.q + ((int64_t)d.b * p.num_q_heads + (int64_t)d.kvh * G + j) * D + 8 * g;
+    auto load_q = [&](bf16x8 (&dst)[S::kSteps], const TileDesc& d) {
+        const uint16_t* qrow = q_ptr + ((int64_t)d.b * p.num_q_heads + (int64_t)d.kvh * G + j) * D + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < S::kSteps; ++ks) {
             u32x4 t = {0u, 0u, 0u, 0u};
             if (j < G) t = *(const u32x4*)(qrow + 32 * ks);
-            qreg[ks] = __builtin_bit_cast(bf16x8, t);
+            dst[ks] = __builtin_bit_cast(bf16x8, t);
         }
     };
-    auto issue_k = [&](const TileDesc& d) {
-        const uint16_t* k0 = p.pool + subtile_base(d, 0) + koff;
-        const uint16_t* k1 = p.pool + subtile_base(d, 1) + koff;
+    auto issue_k = [&](int64_t base0, int64_t base1) {
+        const uint16_t* k0 = pool_ptr + base0 + koff;
+        const uint16_t* k1 = pool_ptr + base1 + koff;
 #pragma unroll
         for (int ks = 0; ks < S::kSteps; ++ks) {
             kreg[0][ks] = __builtin_bit_cast(bf16x8, stream_load(k0 + 32 * ks));
             kreg[1][ks] = __builtin_bit_cast(bf16x8, stream_load(k1 + 32 * ks));
         }
     };
-    auto issue_v = [&](const TileDesc& d) {
-        const uint16_t* v0 = p.pool + subtile_base(d, 0) + v_off + vrow * D + vcol;
-        const uint16_t* v1 = p.pool + subtile_base(d, 1) + v_off + vrow * D + vcol;
+    auto issue_v = [&](int64_t base0, int64_t base1) {
+        const uint16_t* v0 = pool_ptr + base0 + v_off + vrow * D + vcol;
+        const uint16_t* v1 = pool_ptr + base1 + v_off + vrow * D + vcol;
 #pragma unroll
         for (int c = 0; c < S::kVChunks; ++c) {
             const int row16 = (c * S::kRowsPerChunk) & 15;            // first row of the chunk in its subtile
@@ -207,23 +225,29 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
     for (int dt = 0; dt < S::kDTiles; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     fetch_ids(cur);
-    load_q(cur);
-    issue_k(cur);
-    issue_v(cur);
-    bool has_nxt = t_begin + 1 < t_end;
+    load_q(qreg, cur);
+    issue_k(subtile_base(cur, 0), subtile_base(cur, 1));
+    issue_v(subtile_base(cur, 0), subtile_base(cur, 1));
     TileDesc nxt = cur;
-    if (has_nxt) { advance(nxt); fetch_ids(nxt); }
+    if (t_begin + 1 < t_end) { advance(nxt); fetch_ids(nxt); }
+#pragma unroll
+    for (int ks = 0; ks < S::kSteps; ++ks) qnext[ks] = qreg[ks];
+    if (t_begin + 1 < t_end && (nxt.b != cur.b || nxt.kvh != cur.kvh)) load_q(qnext, nxt);
 
-    for (int t = t_begin; t < t_end; ++t) {
-        // block ids are fetched two tiles ahead so that the table lookup is off the critical path
+    // One tile.  HAS_NXT is a compile-time flag: inside the steady-state loop the next tile's loads
+    // are issued unconditionally, which lets the compiler count outstanding loads exactly and keep
+    // them in flight across the whole iteration; the last tile of the run is a second instance.
+    auto do_tile = [&](int t, auto has_nxt_tag) {
+        constexpr bool has_nxt = decltype(has_nxt_tag)::value;
+        // addresses of the next tile from block ids that were fetched a whole tile ago
+        const int64_t nbase0 = has_nxt ? subtile_base(nxt, 0) : 0, nbase1 = has_nxt ? subtile_base(nxt, 1) : 0;
         const bool has_nn = t + 2 < t_end;
-        TileDesc nn = nxt;
-        if (has_nn) { advance(nn); fetch_ids(nn); }
         const bool row_ends = !has_nxt || nxt.b != cur.b || nxt.kvh != cur.kvh;
         const int tok0 = cur.tile * kTileTokens;
         const bool ragged = tok0 + kTileTokens > cur.L;               // wave-uniform
 
-        // ---- S^T = K Q^T for the two 16-token subtiles; then refill the K (and Q) registers
+        // ---- S^T = K Q^T for the two 16-token subtiles; then refill the K registers (and swap in
+        //      the next row's Q, fetch the Q of the row after that)
         f32x4 s[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -233,9 +257,17 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
                 s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[u][ks], qreg[ks], s[u], 0, 0, 0);
         }
         if (has_nxt) {
-            issue_k(nxt);
-            if (row_ends) load_q(nxt);
+            issue_k(nbase0, nbase1);
+            if (row_ends) {                                           // Q of the next row was fetched a tile ago
+#pragma unroll
+                for (int ks = 0; ks < S::kSteps; ++ks) qreg[ks] = qnext[ks];
+            }
         }
+        // block ids two tiles ahead (scalar loads, consumed at the top of the next tile): issued
+        // here, after every address that depends on earlier scalar loads has been formed
+        TileDesc nn = nxt;
+        if (has_nn) { advance(nn); fetch_ids(nn); }
+        if (has_nn && (nn.b != nxt.b || nn.kvh != nxt.kvh)) load_q(qnext, nn);
 
         // ---- online softmax; lane (g, j): s[u][i] is head j, token tok0 + 16u + 4g + i
         float tt[8];
@@ -252,22 +284,26 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
         }
         float mx = fmaxf(fmaxf(fmaxf(tt[0], tt[1]), fmaxf(tt[2], tt[3])),
                          fmaxf(fmaxf(tt[4], tt[5]), fmaxf(tt[6], tt[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);                         // finite: the tile has a valid token
-        const float alpha = fast_exp2(m_run - m_new);
-        m_run = m_new;
+        // wave-uniform: does any lane see a score above its head's running max by more than the slack?
+        if (__builtin_amdgcn_ballot_w64(mx > m_run + kMaxSlack) != 0) {
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);                     // finite: the tile has a valid token
+            const float alpha = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < S::kDTiles; ++dt) oacc[dt] *= alpha;
+        }
         float psum = 0.f;
         bf16x8 pb;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float pe = fast_exp2(tt[e] - m_new);
+            const float pe = fast_exp2(tt[e] - m_run);
             psum += pe;
             pb[e] = (__bf16)pe;
         }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int dt = 0; dt < S::kDTiles; ++dt) oacc[dt] *= alpha;
+        l_run += psum;
 
         // ---- V tile -> LDS (rows past the end are zeroed: 0 * NaN must not reach the sum)
 #pragma unroll
@@ -276,7 +312,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
             if (ragged && tok0 + c * S::kRowsPerChunk + vrow >= cur.L) val = u32x4{0u, 0u, 0u, 0u};
             *(u32x4*)(vt + vw_off + c * S::kRowsPerChunk * S::kPitch) = val;
         }
-        if (has_nxt) issue_v(nxt);
+        if (has_nxt) issue_v(nbase0, nbase1);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -301,7 +337,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
             l_tot += __shfl_xor(l_tot, 32);
             if (j < G) {
                 const int64_t slot = (int64_t)w + (int64_t)cur.b * Hkv + cur.kvh;
-                float* rec = p.ws_records + (slot * G + j) * S::kRecord;
+                float* rec = ws_records + (slot * G + j) * S::kRecord;
 #pragma unroll
                 for (int dt = 0; dt < S::kDTiles; ++dt)
                     *(f32x4*)(rec + 16 * dt + 4 * g) = oacc[dt];      // channels 16dt + 4g .. +3
@@ -314,19 +350,21 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partition_kernel(const 
         }
         cur = nxt;
         nxt = nn;
-        has_nxt = has_nn;
-    }
+    };
+    for (int t = t_begin; t + 1 < t_end; ++t) do_tile(t, std::true_type{});
+    do_tile(t_end - 1, std::false_type{});
 }
 
 // Combines the records of one (sequence, query head) in a fixed order and normalises.
 // The kernel is latency-bound (cold reads of a few KB per workgroup), so every load of a pass is
-// issued before the first use: the 256 threads are kSlices groups of D/4 lanes, a lane owns 4
+// issued before the first use: the threads are kSlices groups of D/4 lanes, a lane owns 4
 // channels, group s takes runs s, s + kSlices, ... of the pass, and the running max and
 // denominators of the pass go through LDS.  Partial sums of the groups are added in group order.
-constexpr int kMergeThreads = 256;
+// Two sizes: 256 threads when there are few (sequence, head) pairs with many records each, 64
+// when there are thousands of pairs with a handful of records (more workgroups resident at once).
 constexpr int kMergePer = 8;                         // records per thread and pass
 
-template <int D>
+template <int D, int kMergeThreads>
 __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const DecodeParams p, int W)
 {
     using S = Shape<D>;
@@ -343,9 +381,9 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const Decod
     const int64_t out0 = ((int64_t)b * p.num_q_heads + h) * D;
     const int n = p.ws_cum[b + 1] - p.ws_cum[b];
     if (n == 0) {                                                     // empty sequence: a row of zeros
-        if (tid < D) {
-            if (p.out_f32) ((float*)p.out)[out0 + tid] = 0.f;
-            else ((uint16_t*)p.out)[out0 + tid] = 0;
+        for (int d = tid; d < D; d += kMergeThreads) {
+            if (p.out_f32) ((float*)p.out)[out0 + d] = 0.f;
+            else ((uint16_t*)p.out)[out0 + d] = 0;
         }
         return;
     }
@@ -394,13 +432,13 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const Decod
     *(f32x4*)(red + slice * D + 4 * c) = acc;
     if (c == 0) redl[slice] = lsum;
     __syncthreads();
-    if (tid < D) {
+    for (int d = tid; d < D; d += kMergeThreads) {
         float o = 0.f, l = 0.f;
 #pragma unroll
-        for (int sidx = 0; sidx < kSlices; ++sidx) { o += red[sidx * D + tid]; l += redl[sidx]; }
+        for (int sidx = 0; sidx < kSlices; ++sidx) { o += red[sidx * D + d]; l += redl[sidx]; }
         o /= l;
-        if (p.out_f32) ((float*)p.out)[out0 + tid] = o;
-        else ((__bf16*)p.out)[out0 + tid] = (__bf16)o;
+        if (p.out_f32) ((float*)p.out)[out0 + d] = o;
+        else ((__bf16*)p.out)[out0 + d] = (__bf16)o;
     }
 }
 
@@ -412,11 +450,14 @@ static hipError_t launch_decode_d(const DecodeParams& p, int workgroups, hipStre
     const size_t scan = (size_t)(p.batch + 1) * sizeof(int);
     const size_t lds = stage > scan ? stage : scan;
     hipLaunchKernelGGL(decode_partition_kernel<D>, dim3((uint32_t)workgroups), dim3(kDecodeThreads), lds,
-                       stream, p);
+                       stream, p, p.q, p.pool, p.block_table, p.context_lens, p.ws_cum, p.ws_records);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_merge_kernel<D>, dim3((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1),
-                       dim3(kMergeThreads), 0, stream, p, workgroups * kDecodeWaves);
+    const dim3 mgrid((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1);
+    if ((int64_t)p.batch * p.num_q_heads >= 2048)
+        hipLaunchKernelGGL((decode_merge_kernel<D, 64>), mgrid, dim3(64), 0, stream, p, workgroups * kDecodeWaves);
+    else
+        hipLaunchKernelGGL((decode_merge_kernel<D, 256>), mgrid, dim3(256), 0, stream, p, workgroups * kDecodeWaves);
     return hipGetLastError();
 }
 
