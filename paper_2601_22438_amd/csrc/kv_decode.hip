@@ -269,6 +269,18 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
         if (has_nn) { advance(nn); fetch_ids(nn); }
         if (has_nn && (nn.b != nxt.b || nn.kvh != nxt.kvh)) load_q(qnext, nn);
 
+        // ---- V tile -> LDS (rows past the end are zeroed: 0 * NaN must not reach the sum)
+#pragma unroll
+        for (int c = 0; c < S::kVChunks; ++c) {
+            u32x4 val = vreg[c];
+            if (ragged && tok0 + c * S::kRowsPerChunk + vrow >= cur.L) val = u32x4{0u, 0u, 0u, 0u};
+            *(u32x4*)(vt + vw_off + c * S::kRowsPerChunk * S::kPitch) = val;
+        }
+        if (has_nxt) issue_v(nbase0, nbase1);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
         // ---- online softmax; lane (g, j): s[u][i] is head j, token tok0 + 16u + 4g + i
         float tt[8];
 #pragma unroll
@@ -304,18 +316,6 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
             pb[e] = (__bf16)pe;
         }
         l_run += psum;
-
-        // ---- V tile -> LDS (rows past the end are zeroed: 0 * NaN must not reach the sum)
-#pragma unroll
-        for (int c = 0; c < S::kVChunks; ++c) {
-            u32x4 val = vreg[c];
-            if (ragged && tok0 + c * S::kRowsPerChunk + vrow >= cur.L) val = u32x4{0u, 0u, 0u, 0u};
-            *(u32x4*)(vt + vw_off + c * S::kRowsPerChunk * S::kPitch) = val;
-        }
-        if (has_nxt) issue_v(nbase0, nbase1);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // ---- O^T += V^T P^T over the tile's 32 tokens, one 16-channel tile at a time
 #pragma unroll
