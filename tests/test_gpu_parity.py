@@ -200,3 +200,62 @@ def test_validate_helpers_catch_bad_device_contents():
     ids = torch.tensor([1, 2, 2], dtype=torch.int32, device="cuda")
     assert kvflow.kv_validate_block_ids(dc.pool, ids, require_distinct=False) == 0
     assert kvflow.kv_validate_block_ids(dc.pool, ids, require_distinct=True) == -7
+
+
+def test_decode_batch_larger_than_one_launch_slice(oracle):
+    """More sequences than one launch scans (4096): the call slices the batch; tiny contexts."""
+    rng = np.random.default_rng(11)
+    lens = rng.integers(0, 40, size=4500).astype(np.int32)
+    case = make(123, 4, 2, 64, 16, lens, MB=3)
+    want = oracle_decode(oracle, case)
+    dc = DeviceCase(case)
+    for dt in (torch.float32, torch.bfloat16):
+        assert_close_to_oracle(dc.decode(dt), want, f"sliced batch {dt}")
+
+
+def test_decode_group_of_16_and_single_kv_head(oracle):
+    case = make(125, 16, 1, 128, 32, [1, 31, 32, 33, 500, 1000], MB=32)
+    want = oracle_decode(oracle, case)
+    dc = DeviceCase(case)
+    for wgs in (0, 2, 9):
+        assert_close_to_oracle(dc.decode(torch.float32, workgroups=wgs), want, f"G=16 workgroups={wgs}")
+
+
+def test_decode_stays_inside_its_workspace_and_output(oracle):
+    """Guard words after the workspace and around the output must survive the call."""
+    case = make(127, 32, 8, 128, 16, [700, 33, 1500, 64], MB=100)
+    g = case.geom
+    dc = DeviceCase(case)
+    nbytes = kvflow.kv_decode_workspace_bytes(case.batch, g.num_q_heads, g.num_kv_heads, g.head_dim, dc.max_len)
+    guard = 4096
+    ws = torch.full((nbytes // 4 + guard,), -123.0, dtype=torch.float32, device="cuda")
+    n_out = case.batch * g.num_q_heads * g.head_dim
+    out = torch.full((n_out + 2 * guard,), -77.0, dtype=torch.float32, device="cuda")
+    view = out[guard:guard + n_out].view(case.batch, g.num_q_heads, g.head_dim)
+    kvflow.kv_decode_attn(view, dc.q, dc.pool, dc.block_table, dc.context_lens, dc.max_len, dc.scale, 0,
+                          ws[:nbytes // 4])
+    torch.cuda.synchronize()
+    assert torch.all(ws[nbytes // 4:] == -123.0)
+    assert torch.all(out[:guard] == -77.0) and torch.all(out[guard + n_out:] == -77.0)
+    assert_close_to_oracle(view, oracle_decode(oracle, case), "guarded")
+    # one byte less of workspace is refused
+    with pytest.raises(kvflow.KvflowError) as err:
+        kvflow.kv_decode_attn(view, dc.q, dc.pool, dc.block_table, dc.context_lens, dc.max_len, dc.scale, 0,
+                              ws[:nbytes // 4 - 1])
+    assert err.value.status == -5
+
+
+def test_decode_large_scores_and_rising_maximum(oracle):
+    """Scores that keep growing along the context force repeated updates of the running maximum."""
+    case = make(129, 8, 2, 64, 16, [300, 77], MB=20)
+    g = case.geom
+    kf = W.bf16_bits_to_f32(case.pool[:, 0]).copy()
+    for b, L in enumerate(case.context_lens):
+        for t in range(int(L)):
+            pid = case.block_table[b, t // g.block_size]
+            kf[pid, :, t % g.block_size, :] *= 0.2 + 0.05 * t          # later keys are much larger
+    case.pool[:, 0] = W.f32_to_bf16_bits(kf)
+    want = oracle_decode(oracle, case)
+    dc = DeviceCase(case)
+    for wgs in (0, 1):
+        assert_close_to_oracle(dc.decode(torch.float32, workgroups=wgs), want, f"rising max workgroups={wgs}")
