@@ -5,7 +5,10 @@ this package; the product package never does.
 """
 from .kv_oracle import (  # noqa: F401
     OracleError,
+    append_tokens,
+    bitmap_words,
     build,
+    collect_dirty,
     decode_attn,
     pack_blocks,
     restore_blocks,

@@ -201,3 +201,52 @@ int kvo_restore_blocks(uint8_t* pool, const uint8_t* replica, int64_t block_byte
 #endif
     return used;
 }
+
+/*
+ * Writing a step's new tokens into the pool and tracking the blocks that became dirty (the
+ * blocks "a step has written", which background replication then ships block by block;
+ * Sec. 3.2 item 3).  One new token per sequence: sequence b's K/V rows (all KV heads) go to
+ * position positions[b] of its context, i.e. to row positions[b] % bs of physical block
+ * block_table[b][positions[b] / bs]; positions[b] < 0 means the sequence takes no token.
+ * The dirty bitmap has one bit per pool block (bit p % 32 of word p / 32) and is OR-ed into,
+ * so it accumulates over steps until it is collected.
+ * k_new, v_new: bf16 [batch][num_kv_heads][head_dim].
+ */
+int kvo_append_tokens(uint16_t* pool, int64_t num_blocks, int num_kv_heads, int block_size, int head_dim,
+                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
+                      int max_blocks_per_seq, const int32_t* positions, int batch, uint32_t* dirty_bitmap)
+{
+    if (num_blocks <= 0 || num_kv_heads <= 0 || block_size <= 0 || head_dim <= 0 || batch < 0) return -2;
+    for (int b = 0; b < batch; ++b) {
+        int t = positions[b];
+        if (t < 0) continue;
+        if ((int64_t)t >= (int64_t)max_blocks_per_seq * block_size) return -3;
+        int32_t p = block_table[(int64_t)b * max_blocks_per_seq + t / block_size];
+        if (p < 0 || p >= num_blocks) return -4;
+    }
+    for (int b = 0; b < batch; ++b) {
+        int t = positions[b];
+        if (t < 0) continue;
+        int64_t p = block_table[(int64_t)b * max_blocks_per_seq + t / block_size];
+        int r = t % block_size;
+        for (int kvh = 0; kvh < num_kv_heads; ++kvh) {
+            for (int which = 0; which < 2; ++which) {
+                const uint16_t* src = (which ? v_new : k_new) + ((int64_t)b * num_kv_heads + kvh) * head_dim;
+                uint16_t* dst = pool + ((((p * 2 + which) * num_kv_heads + kvh) * block_size + r) * (int64_t)head_dim);
+                for (int d = 0; d < head_dim; ++d) dst[d] = src[d];
+            }
+        }
+        dirty_bitmap[p / 32] |= (uint32_t)1 << (p % 32);
+    }
+    return 0;
+}
+
+/* Dirty bitmap -> ascending list of block ids; returns their number.  clear != 0 zeroes the bitmap. */
+int64_t kvo_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* ids_out, int clear)
+{
+    int64_t n = 0;
+    for (int64_t p = 0; p < num_blocks; ++p)
+        if (dirty_bitmap[p / 32] >> (p % 32) & 1u) ids_out[n++] = (int32_t)p;
+    if (clear) for (int64_t w = 0; w < (num_blocks + 31) / 32; ++w) dirty_bitmap[w] = 0;
+    return n;
+}

@@ -57,6 +57,12 @@ def _load():
             f64p, u16p, u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             i32p, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_float,
             i32p, ctypes.c_int64, ctypes.c_int]
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        lib.kvo_append_tokens.restype = ctypes.c_int
+        lib.kvo_append_tokens.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                          u16p, u16p, i32p, ctypes.c_int, i32p, ctypes.c_int, u32p]
+        lib.kvo_collect_dirty.restype = ctypes.c_int64
+        lib.kvo_collect_dirty.argtypes = [u32p, ctypes.c_int64, i32p, ctypes.c_int]
         for fn in (lib.kvo_pack_blocks, lib.kvo_restore_blocks):
             fn.restype = ctypes.c_int
             fn.argtypes = [u8p, u8p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int64, ctypes.c_int]
@@ -150,3 +156,41 @@ def restore_blocks(pool, replica, ids, num_threads=0, return_threads=False):
         _ptr(pb, ctypes.c_uint8), _ptr(rb, ctypes.c_uint8), pb.shape[1], pb.shape[0],
         _ptr(ids, ctypes.c_int32), len(ids), int(num_threads)))
     return used if return_threads else None
+
+
+def bitmap_words(num_blocks: int) -> int:
+    return (int(num_blocks) + 31) // 32
+
+
+def append_tokens(pool, k_new, v_new, block_table, positions, dirty_bitmap):
+    """Write one new token per sequence into the pool (in place) and OR its block into dirty_bitmap.
+
+    pool uint16 [NB][2][Hkv][bs][D] (writable), k_new/v_new uint16 [B][Hkv][D], positions int32 [B]
+    (< 0: no token for that sequence), dirty_bitmap uint32 [ceil(NB/32)] (in place).
+    """
+    if not (pool.flags.c_contiguous and pool.flags.writeable and pool.dtype == np.uint16):
+        raise OracleError("pool must be a writable C-contiguous uint16 array")
+    k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
+    block_table, positions = _c(block_table, np.int32), _c(positions, np.int32)
+    if not (dirty_bitmap.flags.c_contiguous and dirty_bitmap.dtype == np.uint32):
+        raise OracleError("dirty_bitmap must be a C-contiguous uint32 array")
+    NB, two, Hkv, bs, D = pool.shape
+    B = len(positions)
+    if k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D) or block_table.shape[0] != B \
+            or len(dirty_bitmap) != bitmap_words(NB):
+        raise OracleError("inconsistent shapes")
+    _check(_load().kvo_append_tokens(
+        _ptr(pool, ctypes.c_uint16), NB, Hkv, bs, D, _ptr(k_new, ctypes.c_uint16), _ptr(v_new, ctypes.c_uint16),
+        _ptr(block_table, ctypes.c_int32), block_table.shape[1], _ptr(positions, ctypes.c_int32), B,
+        _ptr(dirty_bitmap, ctypes.c_uint32)))
+
+
+def collect_dirty(dirty_bitmap, num_blocks, clear=True):
+    """Ascending ids of the blocks whose bit is set; clears the bitmap in place if asked."""
+    if not (dirty_bitmap.flags.c_contiguous and dirty_bitmap.dtype == np.uint32
+            and len(dirty_bitmap) == bitmap_words(num_blocks)):
+        raise OracleError("dirty_bitmap must be a C-contiguous uint32 array of ceil(NB/32) words")
+    ids = np.empty(int(num_blocks), dtype=np.int32)
+    n = _load().kvo_collect_dirty(_ptr(dirty_bitmap, ctypes.c_uint32), int(num_blocks),
+                                  _ptr(ids, ctypes.c_int32), int(bool(clear)))
+    return ids[:n].copy()

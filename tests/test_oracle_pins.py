@@ -339,3 +339,126 @@ def test_restore_rejects_duplicates_and_bad_ids(oracle):
     bad[1, 0] = case.num_blocks
     with pytest.raises(oracle.OracleError):
         oracle.decode_attn(case.q, case.pool, bad, case.context_lens, 0.125)
+
+
+# ---- next row: appending a step's tokens and tracking dirty blocks ------------------------------
+def new_tokens(case, seed):
+    g = case.geom
+    ss = np.random.SeedSequence(seed).spawn(2)
+    shape = (case.batch, g.num_kv_heads, g.head_dim)
+    return W.normal_bf16(ss[0], shape), W.normal_bf16(ss[1], shape)
+
+
+def test_append_matches_numpy_indexing_and_touches_nothing_else(oracle):
+    case = small_case(seed=51, lens=(5, 31, 80))                    # 31 -> last row of a block, 80 -> row 0 of a new one
+    g = case.geom
+    # the tables must already hold a block for position L: give every sequence one spare block
+    spare = np.setdiff1d(np.arange(case.num_blocks), case.in_use_ids)[:case.batch]
+    table = case.block_table.copy()
+    for b, L in enumerate(case.context_lens):
+        if L % g.block_size == 0:
+            table[b, L // g.block_size] = spare[b]
+    k_new, v_new = new_tokens(case, 1)
+    positions = case.context_lens.copy()
+    positions[1] = -1                                               # sequence 1 takes no token
+    pool = case.pool.copy()
+    bitmap = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    oracle.append_tokens(pool, k_new, v_new, table, positions, bitmap)
+    expect = case.pool.copy()
+    dirty = []
+    for b in (0, 2):
+        t = int(positions[b])
+        pid, r = table[b, t // g.block_size], t % g.block_size
+        expect[pid, 0, :, r, :] = k_new[b]
+        expect[pid, 1, :, r, :] = v_new[b]
+        dirty.append(int(pid))
+    assert np.array_equal(pool, expect)
+    bits = np.unpackbits(bitmap.view(np.uint8), bitorder="little")[:case.num_blocks]
+    assert sorted(np.flatnonzero(bits).tolist()) == sorted(dirty)
+
+
+def test_append_then_decode_equals_contiguous_attention_with_the_token_added(oracle):
+    case = small_case(seed=53, lens=(7, 40, 95))
+    g = case.geom
+    k_new, v_new = new_tokens(case, 2)
+    pool = case.pool.copy()
+    bitmap = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    oracle.append_tokens(pool, k_new, v_new, case.block_table, case.context_lens, bitmap)
+    got = oracle.decode_attn(case.q, pool, case.block_table, case.context_lens + 1, g.scale)
+    # independent: gather the old context contiguously, concatenate the new rows, plain softmax attention
+    ks, vs = gather_contiguous(case)
+    q = W.bf16_bits_to_f32(case.q).astype(np.float64)
+    kn, vn = (W.bf16_bits_to_f32(x).astype(np.float64) for x in (k_new, v_new))
+    for b in range(case.batch):
+        k = np.repeat(np.concatenate([ks[b], kn[b][None]]), g.group, axis=1)
+        v = np.repeat(np.concatenate([vs[b], vn[b][None]]), g.group, axis=1)
+        s = np.einsum("hd,lhd->hl", q[b], k) * float(np.float32(g.scale))
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        np.testing.assert_allclose(got[b], np.einsum("hl,lhd->hd", p, v), rtol=0, atol=1e-12)
+
+
+def test_dirty_bitmap_accumulates_and_collect_is_ascending(oracle):
+    case = small_case(seed=55, lens=(15, 16, 47), NB=70)
+    g = case.geom
+    spare = np.setdiff1d(np.arange(case.num_blocks), case.in_use_ids)
+    table = case.block_table.copy()
+    table[0, 1], table[1, 1], table[2, 3] = spare[:3]               # every sequence crosses into a new block
+    bitmap = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    pool = case.pool.copy()
+    lens = case.context_lens.copy()
+    touched = set()
+    for step in range(3):                                           # three decode steps before one collection
+        k_new, v_new = new_tokens(case, 10 + step)
+        oracle.append_tokens(pool, k_new, v_new, table, lens, bitmap)
+        touched |= {int(table[b, lens[b] // g.block_size]) for b in range(case.batch)}
+        lens += 1
+    ids = oracle.collect_dirty(bitmap, case.num_blocks, clear=False)
+    assert ids.tolist() == sorted(touched) and bitmap.any()
+    again = oracle.collect_dirty(bitmap, case.num_blocks, clear=True)
+    assert again.tolist() == ids.tolist() and not bitmap.any()
+    assert len(oracle.collect_dirty(bitmap, case.num_blocks)) == 0
+    # bit layout: bit p % 32 of word p / 32
+    bitmap[2] = 1 << 5
+    assert oracle.collect_dirty(bitmap, case.num_blocks).tolist() == [69]
+
+
+def test_append_collect_pack_restore_decode_loop(oracle):
+    """The replication loop end to end: only the dirty blocks travel, and the target decodes the same."""
+    case = small_case(seed=57, lens=(20, 50, 100))
+    g = case.geom
+    ids0 = case.in_use_ids
+    # target already holds a replica of the state before the step (under its own ids)
+    rng = np.random.default_rng(3)
+    new_ids = rng.permutation(case.num_blocks)[:len(ids0)].astype(np.int32)
+    remap = np.full(case.num_blocks, -1, np.int32)
+    remap[ids0] = new_ids
+    target = np.full_like(case.pool, 0x7FC0)
+    oracle.restore_blocks(target, oracle.pack_blocks(case.pool, ids0), new_ids)
+    # one step on the source
+    k_new, v_new = new_tokens(case, 4)
+    bitmap = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    src = case.pool.copy()
+    oracle.append_tokens(src, k_new, v_new, case.block_table, case.context_lens, bitmap)
+    dirty = oracle.collect_dirty(bitmap, case.num_blocks)
+    assert len(dirty) == case.batch
+    oracle.restore_blocks(target, oracle.pack_blocks(src, dirty), remap[dirty])
+    table_t = np.where(case.block_table >= 0, remap[np.maximum(case.block_table, 0)], -1).astype(np.int32)
+    a = oracle.decode_attn(case.q, src, case.block_table, case.context_lens + 1, g.scale)
+    b = oracle.decode_attn(case.q, target, table_t, case.context_lens + 1, g.scale)
+    assert np.array_equal(a, b)
+
+
+def test_append_rejects_bad_positions_and_ids(oracle):
+    case = small_case(seed=59, lens=(5, 6, 7))
+    k_new, v_new = new_tokens(case, 5)
+    bitmap = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    pos = case.context_lens.copy()
+    pos[0] = case.block_table.shape[1] * case.geom.block_size      # beyond the table row
+    with pytest.raises(oracle.OracleError):
+        oracle.append_tokens(case.pool.copy(), k_new, v_new, case.block_table, pos, bitmap)
+    pos = case.context_lens.copy()
+    pos[2] = 16                                                     # table entry 1 of sequence 2 is unused (-1)
+    with pytest.raises(oracle.OracleError):
+        oracle.append_tokens(case.pool.copy(), k_new, v_new, case.block_table, pos, bitmap)
+    assert not bitmap.any()
