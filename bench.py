@@ -274,9 +274,23 @@ def bench_replication_mix(args, kvflow, W):
     alone_ms = min(train(30, False) for _ in range(3))
     both_ms = min(train(30, True) for _ in range(3))
     o = {"ms_per_step_decode_only": alone_ms, "ms_per_step_with_pack_on_side_stream": both_ms}
+    # the on-device replication loop of one step: append the new tokens, collect the dirty list, pack it
+    rs = np.random.SeedSequence(4242).spawn(2)
+    k_new = bf16_dev(W.normal_bf16(rs[0], (case.batch, g.num_kv_heads, g.head_dim)))
+    v_new = bf16_dev(W.normal_bf16(rs[1], (case.batch, g.num_kv_heads, g.head_dim)))
+    positions = torch.from_numpy(np.maximum(case.context_lens - 1, 0).astype(np.int32)).cuda()  # rewrite the newest slot
+    bitmap = torch.zeros((case.num_blocks + 31) // 32, dtype=torch.int32, device="cuda")
+    ids_dev = torch.empty(case.batch, dtype=torch.int32, device="cuda")
+    cnt_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
+    a_t = time_calls(lambda: kvflow.kv_append_tokens(pool, k_new, v_new, dec.table, positions, bitmap), 20, 5)
+    c_t = time_calls(lambda: kvflow.kv_collect_dirty(bitmap, case.num_blocks, ids_dev, cnt_dev, False), 20, 5)
+    p_t = time_calls(lambda: kvflow.kv_pack_blocks_counted(replica, pool, ids_dev, cnt_dev), 20, 5)
+    loop = {"append_us": a_t["mean_ms"] * 1e3, "collect_dirty_us": c_t["mean_ms"] * 1e3,
+            "pack_counted_us": p_t["mean_ms"] * 1e3, "dirty_found": int(cnt_dev.item()),
+            "note": "latency-bound helpers (KB to MB of traffic); times include launch and event overhead"}
     kv = case.kv_bytes
     return {
-        "kv_GB": kv / 1e9, "dirty_blocks": n, "pack_payload_MB": n * g.block_bytes / 1e6,
+        "kv_GB": kv / 1e9, "dirty_blocks": n, "replication_loop": loop, "pack_payload_MB": n * g.block_bytes / 1e6,
         "workgroups": dec.workgroups,
         "decode_alone": {**d, "kv_GBps": kv / (d["mean_ms"] * 1e-3) / 1e9,
                          "frac_hbm_peak": kv / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},

@@ -144,6 +144,46 @@ int kv_restore_blocks(const kv_pool_desc* pool, const void* replica, const int32
                       int64_t n, void* stream);
 
 /*
+ * Appending a decode step's new tokens and tracking dirty blocks: the step that produces "the
+ * blocks a step has written" which background replication then ships (Sec. 3.2 item 3).
+ *
+ * kv_append_tokens: one new token per sequence.  For every b with positions[b] >= 0 the rows
+ * k_new[b], v_new[b] (all KV heads) are written to position t = positions[b] of sequence b, i.e.
+ * row t % bs of block block_table[b][t / bs], and that block's bit is OR-ed into dirty_bitmap.
+ *   k_new, v_new   bf16 [batch][num_kv_heads][head_dim], 16-byte aligned, read
+ *   positions      int32 [batch], read; < 0 = the sequence takes no token
+ *   dirty_bitmap   uint32 [ceil(num_blocks / 32)], bit p % 32 of word p / 32 stands for block p;
+ *                  read-modify-written (atomic OR), so it accumulates over steps until collected.
+ *                  The caller zeroes it once after allocation.
+ * Preconditions: positions[b] < max_blocks_per_seq * bs; the table entry it selects is a valid
+ * block id; no two sequences map to the same (block, row).
+ */
+int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_new,
+                     const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* positions,
+                     int32_t batch, uint32_t* dirty_bitmap, void* stream);
+
+/*
+ * kv_collect_dirty: dirty bitmap -> ascending list of block ids, on the device.
+ *   dirty_ids    int32 [capacity], written: the first min(count, capacity) dirty ids, ascending
+ *   dirty_count  int32 [1], written: the number of dirty blocks (may exceed capacity: the caller
+ *                sized the list too small and sees it here)
+ *   clear        non-zero: the bitmap is zeroed for the next round of steps
+ * One workgroup; meant for pools of up to a few million blocks.
+ */
+int kv_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* dirty_ids, int64_t capacity,
+                     int32_t* dirty_count, int32_t clear, void* stream);
+
+/*
+ * kv_pack_blocks with the list length taken from device memory, so that the loop
+ * append -> collect -> pack runs without the host seeing the list:
+ *     replica[i] <- pool[block_ids[i]]   for i in [0, min(*count, max_n)).
+ *   count   int32 [1], device, read when the kernel runs
+ *   max_n   host bound of the list length; sizes the launch and the replica buffer
+ */
+int kv_pack_blocks_counted(void* replica, const kv_pool_desc* pool, const int32_t* block_ids,
+                           const int32_t* count, int64_t max_n, void* stream);
+
+/*
  * Debug helpers: copy the device arrays to the host (synchronising `stream`)
  * and check the preconditions above.  Return KV_OK, KV_ERR_CONTENT, or an
  * argument error.  Not for the hot path.

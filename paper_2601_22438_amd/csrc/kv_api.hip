@@ -58,7 +58,7 @@ int32_t resolve_workgroups(int32_t batch, int32_t num_kv_heads, int32_t max_cont
 size_t cum_bytes(int64_t batch_slice) { return (size_t)(((batch_slice + 1) * 4 + 15) / 16 * 16); }
 
 int copy_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n,
-                bool to_replica, void* stream)
+                const int32_t* count, bool to_replica, void* stream)
 {
     int rc = check_pool(pool);
     if (rc != KV_OK) return rc;
@@ -66,7 +66,7 @@ int copy_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_id
     if (n == 0) return KV_OK;
     if (!replica || !block_ids) return KV_ERR_NULL;
     if (!aligned16(replica)) return KV_ERR_ALIGN;
-    hipError_t e = launch_copy_blocks(replica, pool->base, block_bytes_of(pool), block_ids, n,
+    hipError_t e = launch_copy_blocks(replica, pool->base, block_bytes_of(pool), block_ids, n, count,
                                       to_replica, (hipStream_t)stream);
     return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }
@@ -157,13 +157,46 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
 
 int kv_pack_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n, void* stream)
 {
-    return copy_blocks(replica, pool, block_ids, n, true, stream);
+    return copy_blocks(replica, pool, block_ids, n, nullptr, true, stream);
 }
 
 int kv_restore_blocks(const kv_pool_desc* pool, const void* replica, const int32_t* block_ids, int64_t n,
                       void* stream)
 {
-    return copy_blocks(const_cast<void*>(replica), pool, block_ids, n, false, stream);
+    return copy_blocks(const_cast<void*>(replica), pool, block_ids, n, nullptr, false, stream);
+}
+
+int kv_pack_blocks_counted(void* replica, const kv_pool_desc* pool, const int32_t* block_ids,
+                           const int32_t* count, int64_t max_n, void* stream)
+{
+    if (max_n > 0 && !count) return KV_ERR_NULL;
+    return copy_blocks(replica, pool, block_ids, max_n, count, true, stream);
+}
+
+int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_new,
+                     const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* positions,
+                     int32_t batch, uint32_t* dirty_bitmap, void* stream)
+{
+    int rc = check_pool(pool);
+    if (rc != KV_OK) return rc;
+    if (batch < 0 || max_blocks_per_seq <= 0) return KV_ERR_SHAPE;
+    if (batch == 0) return KV_OK;
+    if (!k_new || !v_new || !block_table || !positions || !dirty_bitmap) return KV_ERR_NULL;
+    if (!aligned16(k_new) || !aligned16(v_new)) return KV_ERR_ALIGN;
+    hipError_t e = launch_append_tokens((uint16_t*)pool->base, (const uint16_t*)k_new, (const uint16_t*)v_new,
+                                        block_table, max_blocks_per_seq, positions, batch, pool->num_kv_heads,
+                                        pool->block_size, pool->head_dim, dirty_bitmap, (hipStream_t)stream);
+    return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
+}
+
+int kv_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* dirty_ids, int64_t capacity,
+                     int32_t* dirty_count, int32_t clear, void* stream)
+{
+    if (num_blocks <= 0 || capacity < 0 || num_blocks > 0x7FFFFFFF) return KV_ERR_SHAPE;
+    if (!dirty_bitmap || !dirty_count || (capacity > 0 && !dirty_ids)) return KV_ERR_NULL;
+    hipError_t e = launch_collect_dirty(dirty_bitmap, num_blocks, dirty_ids, capacity, dirty_count, clear != 0,
+                                        (hipStream_t)stream);
+    return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }
 
 int kv_validate_decode(const kv_pool_desc* pool, const int32_t* block_table, int32_t max_blocks_per_seq,

@@ -35,10 +35,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t block_rsrc(const char* base, u
 template <int U, bool TO_REPLICA>
 __global__ __launch_bounds__(kCopyThreads) void copy_blocks_kernel(
     char* __restrict__ replica, char* __restrict__ pool, const int32_t* __restrict__ block_ids,
-    uint32_t block_bytes, uint32_t segs_per_block)
+    uint32_t block_bytes, uint32_t segs_per_block, int64_t first, const int32_t* __restrict__ count)
 {
     const uint32_t seg = blockIdx.x % segs_per_block;
     const int64_t i = blockIdx.x / segs_per_block + (int64_t)blockIdx.y * (kMaxGridX / segs_per_block);
+    // a device-side count (list produced on the GPU) cuts the list short; first = entries before this launch
+    if (count && first + i >= *count) return;
     const int64_t id = block_ids[i];
     const char* src = TO_REPLICA ? pool + id * block_bytes : replica + i * block_bytes;
     char* dst = TO_REPLICA ? replica + i * block_bytes : pool + id * block_bytes;
@@ -60,7 +62,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_blocks_kernel(
 
 template <int U, bool TO_REPLICA>
 static hipError_t launch_dir(char* replica, char* pool, size_t block_bytes, const int32_t* block_ids,
-                             int64_t n, hipStream_t stream)
+                             int64_t n, const int32_t* count, hipStream_t stream)
 {
     const uint32_t seg_bytes = kCopyThreads * 16 * U;
     const uint32_t segs = (uint32_t)((block_bytes + seg_bytes - 1) / seg_bytes);
@@ -82,7 +84,8 @@ static hipError_t launch_dir(char* replica, char* pool, size_t block_bytes, cons
             take = left;
         }
         hipLaunchKernelGGL((copy_blocks_kernel<U, TO_REPLICA>), grid, dim3(kCopyThreads), 0, stream,
-                           replica + done * block_bytes, pool, block_ids + done, (uint32_t)block_bytes, segs);
+                           replica + done * block_bytes, pool, block_ids + done, (uint32_t)block_bytes, segs,
+                           done, count);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         done += take;
@@ -91,13 +94,13 @@ static hipError_t launch_dir(char* replica, char* pool, size_t block_bytes, cons
 }
 
 hipError_t launch_copy_blocks(void* replica, void* pool, size_t block_bytes, const int32_t* block_ids,
-                              int64_t n, bool to_replica, hipStream_t stream)
+                              int64_t n, const int32_t* count, bool to_replica, hipStream_t stream)
 {
     if (block_bytes == 0 || block_bytes > 0x7FFFFFF0u) return hipErrorInvalidValue;
     if (block_bytes / (kCopyThreads * 16) + 1 > kMaxGridX) return hipErrorInvalidValue;
     if (to_replica)
-        return launch_dir<kPackUnroll, true>((char*)replica, (char*)pool, block_bytes, block_ids, n, stream);
-    return launch_dir<kRestoreUnroll, false>((char*)replica, (char*)pool, block_bytes, block_ids, n, stream);
+        return launch_dir<kPackUnroll, true>((char*)replica, (char*)pool, block_bytes, block_ids, n, count, stream);
+    return launch_dir<kRestoreUnroll, false>((char*)replica, (char*)pool, block_bytes, block_ids, n, count, stream);
 }
 
 }  // namespace kvflow

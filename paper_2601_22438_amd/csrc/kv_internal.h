@@ -40,8 +40,17 @@ struct DecodeParams {
 
 hipError_t launch_decode(const DecodeParams& p, int head_dim, int workgroups, hipStream_t stream);
 
-// dst/src are the replica and the pool; to_replica selects the direction.
+// dst/src are the replica and the pool; to_replica selects the direction.  count (device, may be
+// NULL) limits the list to its first *count entries; n then is the launch bound.
 hipError_t launch_copy_blocks(void* replica, void* pool, size_t block_bytes, const int32_t* block_ids,
-                              int64_t n, bool to_replica, hipStream_t stream);
+                              int64_t n, const int32_t* count, bool to_replica, hipStream_t stream);
+
+hipError_t launch_append_tokens(uint16_t* pool, const uint16_t* k_new, const uint16_t* v_new,
+                                const int32_t* block_table, int max_blocks_per_seq, const int32_t* positions,
+                                int batch, int num_kv_heads, int block_size, int head_dim,
+                                uint32_t* dirty_bitmap, hipStream_t stream);
+
+hipError_t launch_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* ids_out, int64_t capacity,
+                                int32_t* count_out, int clear, hipStream_t stream);
 
 }  // namespace kvflow

@@ -56,6 +56,12 @@ def load() -> ctypes.CDLL:
     lib.kv_pack_blocks.argtypes = [P, PD, P, I64, P]
     lib.kv_restore_blocks.restype = ctypes.c_int
     lib.kv_restore_blocks.argtypes = [PD, P, P, I64, P]
+    lib.kv_pack_blocks_counted.restype = ctypes.c_int
+    lib.kv_pack_blocks_counted.argtypes = [P, PD, P, P, I64, P]
+    lib.kv_append_tokens.restype = ctypes.c_int
+    lib.kv_append_tokens.argtypes = [PD, P, P, P, I32, P, I32, P, P]
+    lib.kv_collect_dirty.restype = ctypes.c_int
+    lib.kv_collect_dirty.argtypes = [P, I64, P, I64, P, I32, P]
     lib.kv_validate_decode.restype = ctypes.c_int
     lib.kv_validate_decode.argtypes = [PD, P, I32, P, I32, I32, P]
     lib.kv_validate_block_ids.restype = ctypes.c_int
@@ -132,6 +138,26 @@ def kv_restore_blocks(pool, replica, block_ids, n=None, stream=None) -> None:
     n = block_ids.numel() if n is None else int(n)
     _check(load().kv_restore_blocks(ctypes.byref(pool_desc(pool)), _ptr(replica), _ptr(block_ids), n,
                                     _stream_handle(stream)))
+
+
+def kv_pack_blocks_counted(replica, pool, block_ids, count, max_n=None, stream=None) -> None:
+    """Enqueue replica[i] <- pool[block_ids[i]] for i < min(count[0], max_n); count lives on the device."""
+    max_n = block_ids.numel() if max_n is None else int(max_n)
+    _check(load().kv_pack_blocks_counted(_ptr(replica), ctypes.byref(pool_desc(pool)), _ptr(block_ids),
+                                         _ptr(count), max_n, _stream_handle(stream)))
+
+
+def kv_append_tokens(pool, k_new, v_new, block_table, positions, dirty_bitmap, stream=None) -> None:
+    """Enqueue the write of one new K/V token per sequence and the update of the dirty bitmap."""
+    _check(load().kv_append_tokens(ctypes.byref(pool_desc(pool)), _ptr(k_new), _ptr(v_new), _ptr(block_table),
+                                   block_table.shape[1], _ptr(positions), positions.numel(),
+                                   _ptr(dirty_bitmap), _stream_handle(stream)))
+
+
+def kv_collect_dirty(dirty_bitmap, num_blocks, dirty_ids, dirty_count, clear=True, stream=None) -> None:
+    """Enqueue bitmap -> ascending id list (dirty_ids) and its length (dirty_count[0]), both on the device."""
+    _check(load().kv_collect_dirty(_ptr(dirty_bitmap), int(num_blocks), _ptr(dirty_ids), dirty_ids.numel(),
+                                   _ptr(dirty_count), int(bool(clear)), _stream_handle(stream)))
 
 
 def kv_validate_decode(pool, block_table, context_lens, max_context_len, stream=None) -> int:

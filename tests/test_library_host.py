@@ -117,3 +117,25 @@ def test_status_strings(lib):
     texts = {kvflow.kv_status_string(s) for s in range(-7, 1)}
     assert len(texts) == 8 and "unknown status" not in texts
     assert kvflow.kv_status_string(-99) == "unknown status"
+
+
+def test_append_collect_counted_pack_reject_bad_arguments(lib):
+    from paper_2601_22438_amd import kvflow
+    ok = desc(kvflow)
+    ap = lambda p=ok, k=0x20000, v=0x30000, tb=0x40000, mb=4, pos=0x50000, b=2, bm=0x60000: \
+        lib.kv_append_tokens(ctypes.byref(p), k, v, tb, mb, pos, b, bm, None)
+    assert ap(b=0) == 0
+    assert ap(k=0) == -1 and ap(v=0) == -1 and ap(tb=0) == -1 and ap(pos=0) == -1 and ap(bm=0) == -1
+    assert ap(p=desc(kvflow, base=0)) == -1
+    assert ap(b=-1) == -2 and ap(mb=0) == -2
+    assert ap(p=desc(kvflow, d=48)) == -3
+    assert ap(k=0x20008) == -4
+    co = lambda bm=0x60000, nb=100, ids=0x70000, cap=10, cnt=0x80000: \
+        lib.kv_collect_dirty(bm, nb, ids, cap, cnt, 1, None)
+    assert co(bm=0) == -1 and co(cnt=0) == -1 and co(ids=0) == -1
+    assert co(nb=0) == -2 and co(cap=-1) == -2
+    pc = lambda rep=0x20000, ids=0x30000, cnt=0x40000, n=3: \
+        lib.kv_pack_blocks_counted(rep, ctypes.byref(ok), ids, cnt, n, None)
+    assert pc(n=0) == 0
+    assert pc(cnt=0) == -1 and pc(rep=0) == -1 and pc(ids=0) == -1
+    assert pc(n=-2) == -2
