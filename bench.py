@@ -251,18 +251,22 @@ def bench_replication_mix(args, kvflow, W):
     main = torch.cuda.current_stream()
 
     def train(n_iter, with_pack):
-        """n_iter decode steps back to back on the main stream; with_pack adds, for every step, a pack
-        on the side stream that starts when the step starts.  Returns ms per step."""
+        """n_iter decode steps back to back on the main stream.  with_pack = "side": every step also
+        starts a pack on the side stream, ordered after the previous step by an event (as a pack of
+        freshly written blocks has to be); "same": the pack follows the decode on the main stream.
+        Returns ms per step."""
         t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0.record(main)
         for _ in range(n_iter):
-            if with_pack:
+            if with_pack == "side":
                 ev = torch.cuda.Event()
                 ev.record(main)
                 side.wait_event(ev)
                 kvflow.kv_pack_blocks(replica, pool, ids, stream=side)
             dec.run()
-        if with_pack:
+            if with_pack == "same":
+                kvflow.kv_pack_blocks(replica, pool, ids)
+        if with_pack == "side":
             done = torch.cuda.Event()
             done.record(side)
             main.wait_event(done)
@@ -270,10 +274,13 @@ def bench_replication_mix(args, kvflow, W):
         torch.cuda.synchronize()
         return t0.elapsed_time(t1) / n_iter
 
-    train(5, True)
-    alone_ms = min(train(30, False) for _ in range(3))
-    both_ms = min(train(30, True) for _ in range(3))
-    o = {"ms_per_step_decode_only": alone_ms, "ms_per_step_with_pack_on_side_stream": both_ms}
+    train(5, "side")
+    alone_ms = min(train(30, None) for _ in range(3))
+    both_ms = min(train(30, "side") for _ in range(3))
+    same_ms = min(train(30, "same") for _ in range(3))
+    o = {"ms_per_step_decode_only": alone_ms, "ms_per_step_with_pack_on_side_stream": both_ms,
+         "ms_per_step_with_pack_on_same_stream": same_ms,
+         "note": "the side-stream figure includes one event record/wait per step between the two streams"}
     # the on-device replication loop of one step: append the new tokens, collect the dirty list, pack it
     rs = np.random.SeedSequence(4242).spawn(2)
     k_new = bf16_dev(W.normal_bf16(rs[0], (case.batch, g.num_kv_heads, g.head_dim)))
@@ -288,15 +295,53 @@ def bench_replication_mix(args, kvflow, W):
     loop = {"append_us": a_t["mean_ms"] * 1e3, "collect_dirty_us": c_t["mean_ms"] * 1e3,
             "pack_counted_us": p_t["mean_ms"] * 1e3, "dirty_found": int(cnt_dev.item()),
             "note": "latency-bound helpers (KB to MB of traffic); times include launch and event overhead"}
+    # pack into pinned host memory (a transport buffer on the far side of PCIe): rate, and what a
+    # decode step costs while such a pack is running beside it.  The list is long enough (2048
+    # blocks, 268 MB) for the pack to outlast the measured decode steps.
+    n_host = min(2048, len(case.in_use_ids))
+    host_ids = torch.from_numpy(case.in_use_ids[:n_host].copy()).cuda()
+    host_replica = torch.empty((n_host,) + pool.shape[1:], dtype=torch.bfloat16).pin_memory()
+    host_payload = n_host * g.block_bytes
+
+    def decode_steps_beside(launch_pack, steps=24):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        done = torch.cuda.Event()
+        torch.cuda.synchronize()
+        if launch_pack is not None:
+            ev = torch.cuda.Event()
+            ev.record(main)
+            side.wait_event(ev)
+            launch_pack()
+            done.record(side)
+        for i in range(steps):
+            evs[i].record(main)
+            dec.run()
+        evs[steps].record(main)
+        evs[steps].synchronize()
+        still_running = launch_pack is not None and not done.query()
+        torch.cuda.synchronize()
+        ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(4, steps)]      # skip the start-up steps
+        return float(np.median(ms)), still_running
+
+    host = {"blocks": n_host, "payload_MB": host_payload / 1e6}
+    base_ms, _ = decode_steps_beside(None)
+    host["decode_step_ms_alone"] = base_ms
+    fn = lambda: kvflow.kv_pack_blocks(host_replica, pool, host_ids, stream=side)
+    t = time_calls(lambda: fn() or side.synchronize(), 3, 1)
+    step_ms, covered = decode_steps_beside(fn, steps=max(8, int(0.6 * t["mean_ms"] / base_ms)))
+    host.update({"pack_ms": t["mean_ms"], "payload_GBps": host_payload / (t["mean_ms"] * 1e-3) / 1e9,
+                 "decode_step_ms_meanwhile": step_ms, "pack_outlasted_the_steps": covered,
+                 "decode_slowdown_pct": 100.0 * (step_ms / base_ms - 1.0)})
     kv = case.kv_bytes
     return {
-        "kv_GB": kv / 1e9, "dirty_blocks": n, "replication_loop": loop, "pack_payload_MB": n * g.block_bytes / 1e6,
+        "kv_GB": kv / 1e9, "dirty_blocks": n, "replication_loop": loop, "pack_to_host": host, "pack_payload_MB": n * g.block_bytes / 1e6,
         "workgroups": dec.workgroups,
         "decode_alone": {**d, "kv_GBps": kv / (d["mean_ms"] * 1e-3) / 1e9,
                          "frac_hbm_peak": kv / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "pack_alone": {**p, **copy_rates(n * g.block_bytes, p["mean_ms"])},
         "back_to_back_steps": o,
         "decode_slowdown_pct": 100.0 * (both_ms / alone_ms - 1.0),
+        "same_stream_slowdown_pct": 100.0 * (same_ms / alone_ms - 1.0),
     }
 
 
