@@ -303,35 +303,47 @@ def bench_replication_mix(args, kvflow, W):
     host_replica = torch.empty((n_host,) + pool.shape[1:], dtype=torch.bfloat16).pin_memory()
     host_payload = n_host * g.block_bytes
 
-    def decode_steps_beside(launch_pack, steps=24):
+    def decode_steps_beside(launch_pack, steps=40):
+        """`steps` decode steps on the main stream while launch_pack() runs on the side stream.
+        Returns (median ms of the steps after the first four, total ms of all steps, side-stream ms)."""
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-        done = torch.cuda.Event()
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         if launch_pack is not None:
             ev = torch.cuda.Event()
             ev.record(main)
             side.wait_event(ev)
+            s0.record(side)
             launch_pack()
-            done.record(side)
+            s1.record(side)
         for i in range(steps):
             evs[i].record(main)
             dec.run()
         evs[steps].record(main)
-        evs[steps].synchronize()
-        still_running = launch_pack is not None and not done.query()
         torch.cuda.synchronize()
-        ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(4, steps)]      # skip the start-up steps
-        return float(np.median(ms)), still_running
+        ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+        return float(np.median(ms[4:])), float(sum(ms)), (s0.elapsed_time(s1) if launch_pack is not None else 0.0)
 
-    host = {"blocks": n_host, "payload_MB": host_payload / 1e6}
-    base_ms, _ = decode_steps_beside(None)
-    host["decode_step_ms_alone"] = base_ms
-    fn = lambda: kvflow.kv_pack_blocks(host_replica, pool, host_ids, stream=side)
-    t = time_calls(lambda: fn() or side.synchronize(), 3, 1)
-    step_ms, covered = decode_steps_beside(fn, steps=max(8, int(0.6 * t["mean_ms"] / base_ms)))
-    host.update({"pack_ms": t["mean_ms"], "payload_GBps": host_payload / (t["mean_ms"] * 1e-3) / 1e9,
-                 "decode_step_ms_meanwhile": step_ms, "pack_outlasted_the_steps": covered,
-                 "decode_slowdown_pct": 100.0 * (step_ms / base_ms - 1.0)})
+    dev_staging = torch.empty((n_host,) + pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+
+    def direct():
+        kvflow.kv_pack_blocks(host_replica, pool, host_ids, stream=side)
+
+    def staged():
+        kvflow.kv_pack_blocks(dev_staging, pool, host_ids, stream=side)
+        with torch.cuda.stream(side):
+            host_replica.copy_(dev_staging, non_blocking=True)       # DMA engine, not the compute units
+
+    host = {"blocks": n_host, "payload_MB": host_payload / 1e6, "decode_steps": 40}
+    decode_steps_beside(None)
+    base_med, base_sum, _ = decode_steps_beside(None)
+    host["decode_alone"] = {"median_step_ms": base_med, "total_ms": base_sum}
+    for label, fn in (("pack_kernel_writes_host_memory", direct), ("pack_to_device_staging_then_dma", staged)):
+        decode_steps_beside(fn)
+        med, tot, side_ms = decode_steps_beside(fn)
+        host[label] = {"transfer_ms": side_ms, "payload_GBps": host_payload / (side_ms * 1e-3) / 1e9,
+                       "median_step_ms_meanwhile": med, "steady_slowdown_pct": 100.0 * (med / base_med - 1.0),
+                       "total_delay_of_the_steps_ms": tot - base_sum}
     kv = case.kv_bytes
     return {
         "kv_GB": kv / 1e9, "dirty_blocks": n, "replication_loop": loop, "pack_to_host": host, "pack_payload_MB": n * g.block_bytes / 1e6,

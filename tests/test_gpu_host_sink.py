@@ -36,6 +36,24 @@ def test_pack_to_pinned_host_and_restore_from_it(oracle):
     assert np.array_equal(bits_of(target), expect)
 
 
+def test_staged_transfer_pack_to_device_then_dma_to_host(oracle):
+    """The transfer path that leaves decode alone: pack at HBM speed into a device staging replica,
+    then a DMA copy to the pinned host buffer on the same side stream."""
+    g = W.Geometry(64, 8, 128, 32)
+    case = W.make_decode_case("t", 305, g, np.array([700, 90, 2000], np.int32), dirty="fraction", n_dirty=25)
+    pool = bf16_tensor(case.pool)
+    ids = torch.from_numpy(case.dirty_ids).cuda()
+    staging = torch.empty((len(case.dirty_ids),) + pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+    host = torch.zeros(staging.shape, dtype=torch.bfloat16).pin_memory()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    kvflow.kv_pack_blocks(staging, pool, ids, stream=side)
+    with torch.cuda.stream(side):
+        host.copy_(staging, non_blocking=True)
+    side.synchronize()
+    assert np.array_equal(host_bits(host), oracle.pack_blocks(case.pool, case.dirty_ids))
+
+
 def test_decode_is_unchanged_while_packing_to_host_on_a_side_stream(oracle):
     case = W.llama8b_layer(shrink=2)
     dc = DeviceCase(case)
