@@ -16,7 +16,9 @@
  *     replication target continues requests "from the replicated state".
  *
  * All floating point is IEEE double.  Inputs are bf16 bit patterns (uint16)
- * widened exactly: bf16 -> fp32 by a 16-bit left shift -> double.
+ * widened exactly: bf16 -> fp32 by a 16-bit left shift -> double.  The pool may
+ * instead hold FP8 E4M3 bit patterns (uint8) with one fp32 scale for K and one
+ * for V; they are decoded exactly and multiplied by the scale in double.
  *
  * Pool layout: [num_blocks][2][num_kv_heads][block_size][head_dim] bf16,
  * index 0 of the second axis is K, index 1 is V.  Only the accessor kv_at()
@@ -34,9 +36,11 @@
 #endif
 
 typedef struct {
-    const uint16_t* base;
+    const void* base;
     int64_t num_blocks;
     int num_kv_heads, block_size, head_dim;
+    int fp8;                /* 0: bf16 elements; 1: OCP FP8 E4M3 elements */
+    double k_scale, v_scale; /* FP8 pools store value / scale; 1 for bf16 */
 } pool_view;
 
 static double bf16_to_double(uint16_t bits)
@@ -47,11 +51,29 @@ static double bf16_to_double(uint16_t bits)
     return (double)f;
 }
 
-/* which: 0 = key, 1 = value; p physical block; kvh KV head; r row in block; d channel */
+/*
+ * OCP 8-bit floating point, E4M3 variant: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits;
+ * exponent field 0 is subnormal (m/8 * 2^-6), there are no infinities, and exponent 15 with
+ * mantissa 7 is NaN, so the largest magnitude is 1.75 * 2^8 = 448.
+ */
+static double fp8_e4m3_to_double(uint8_t bits)
+{
+    int e = (bits >> 3) & 15, m = bits & 7;
+    double v;
+    if (e == 15 && m == 7) v = NAN;
+    else if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return (bits & 0x80) ? -v : v;
+}
+
+/* which: 0 = key, 1 = value; p physical block; kvh KV head; r row in block; d channel.
+ * For an FP8 pool the stored number times the pool's K or V scale is the value. */
 static double kv_at(const pool_view* pv, int which, int64_t p, int kvh, int r, int d)
 {
     int64_t idx = (((p * 2 + which) * pv->num_kv_heads + kvh) * pv->block_size + r) * (int64_t)pv->head_dim + d;
-    return bf16_to_double(pv->base[idx]);
+    if (pv->fp8)
+        return fp8_e4m3_to_double(((const uint8_t*)pv->base)[idx]) * (which ? pv->v_scale : pv->k_scale);
+    return bf16_to_double(((const uint16_t*)pv->base)[idx]);
 }
 
 /* One (sequence, query head) output row.  s and w are caller scratch of >= L doubles. */
@@ -109,8 +131,8 @@ static int check_decode_args(int64_t num_blocks, int num_kv_heads, int block_siz
  * is [n_rows][head_dim].  Returns the number of threads used (>= 1) or a
  * negative error.
  */
-int kvo_decode_attn(double* out, const uint16_t* q, const uint16_t* pool, int64_t num_blocks,
-                    int num_kv_heads, int block_size, int head_dim,
+int kvo_decode_attn(double* out, const uint16_t* q, const void* pool, int kv_fp8, float k_scale, float v_scale,
+                    int64_t num_blocks, int num_kv_heads, int block_size, int head_dim,
                     const int32_t* block_table, int max_blocks_per_seq,
                     const int32_t* context_lens, int batch, int num_q_heads, float scale,
                     const int32_t* rows, int64_t n_rows, int num_threads)
@@ -118,7 +140,8 @@ int kvo_decode_attn(double* out, const uint16_t* q, const uint16_t* pool, int64_
     int rc = check_decode_args(num_blocks, num_kv_heads, block_size, head_dim, block_table,
                                max_blocks_per_seq, context_lens, batch, num_q_heads);
     if (rc) return rc;
-    pool_view pv = { pool, num_blocks, num_kv_heads, block_size, head_dim };
+    pool_view pv = { pool, num_blocks, num_kv_heads, block_size, head_dim, kv_fp8 != 0,
+                     kv_fp8 ? (double)k_scale : 1.0, kv_fp8 ? (double)v_scale : 1.0 };
     const int G = num_q_heads / num_kv_heads;
     const int64_t total = rows ? n_rows : (int64_t)batch * num_q_heads;
     int maxL = 1;

@@ -54,7 +54,8 @@ def _load():
         f64p = ctypes.POINTER(ctypes.c_double)
         lib.kvo_decode_attn.restype = ctypes.c_int
         lib.kvo_decode_attn.argtypes = [
-            f64p, u16p, u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            f64p, u16p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_float,
+            ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             i32p, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_float,
             i32p, ctypes.c_int64, ctypes.c_int]
         u32p = ctypes.POINTER(ctypes.c_uint32)
@@ -88,11 +89,13 @@ def _c(a, dtype) -> np.ndarray:
 
 
 def decode_attn(q, pool, block_table, context_lens, scale, rows=None, num_threads=0,
-                return_threads=False):
+                return_threads=False, k_scale=1.0, v_scale=1.0):
     """fp64 paged decode attention.
 
     q            uint16 [B][Hq][D]              bf16 bit patterns
-    pool         uint16 [NB][2][Hkv][bs][D]     bf16 bit patterns, axis 1: 0 = K, 1 = V
+    pool         uint16 [NB][2][Hkv][bs][D]     bf16 bit patterns, axis 1: 0 = K, 1 = V; or uint8 of the
+                                                same shape: FP8 E4M3 patterns, value = stored * k_scale
+                                                (K) or * v_scale (V), scales rounded to fp32
     block_table  int32  [B][MB]                 logical -> physical block, unused entries ignored
     context_lens int32  [B]
     scale        python/np float; rounded to fp32 and then widened to double
@@ -100,7 +103,10 @@ def decode_attn(q, pool, block_table, context_lens, scale, rows=None, num_thread
     Returns float64 [B][Hq][D] (or [n][D]).
     """
     q = _c(q, np.uint16)
-    pool = _c(pool, np.uint16)
+    pool = np.ascontiguousarray(pool)
+    if pool.dtype not in (np.uint16, np.uint8):
+        raise TypeError("pool must be uint16 (bf16) or uint8 (FP8 E4M3)")
+    fp8 = pool.dtype == np.uint8
     block_table = _c(block_table, np.int32)
     context_lens = _c(context_lens, np.int32)
     B, Hq, D = q.shape
@@ -117,8 +123,8 @@ def decode_attn(q, pool, block_table, context_lens, scale, rows=None, num_thread
         out = np.empty((len(rows), D), dtype=np.float64)
         rows_p, n_rows = _ptr(rows, ctypes.c_int32), len(rows)
     used = _check(_load().kvo_decode_attn(
-        _ptr(out, ctypes.c_double), _ptr(q, ctypes.c_uint16), _ptr(pool, ctypes.c_uint16),
-        NB, Hkv, bs, D, _ptr(block_table, ctypes.c_int32), block_table.shape[1],
+        _ptr(out, ctypes.c_double), _ptr(q, ctypes.c_uint16), pool.ctypes.data_as(ctypes.c_void_p),
+        int(fp8), float(np.float32(k_scale)), float(np.float32(v_scale)), NB, Hkv, bs, D, _ptr(block_table, ctypes.c_int32), block_table.shape[1],
         _ptr(context_lens, ctypes.c_int32), B, Hq, float(np.float32(scale)),
         rows_p, n_rows, int(num_threads)))
     return (out, used) if return_threads else out

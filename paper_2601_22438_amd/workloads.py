@@ -64,12 +64,64 @@ def normal_bf16(seed_seq: np.random.SeedSequence, shape) -> np.ndarray:
     return out.reshape(shape)
 
 
+def f32_to_fp8_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to OCP FP8 E4M3 (1-4-3, bias 7, no infinities; nearest, ties to even,
+    magnitudes beyond 448 saturate to 448); returns uint8 bit patterns.  Inputs must be finite."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    sign = np.signbit(x).astype(np.uint8) << 7
+    a = np.minimum(np.abs(x).astype(np.float64), 448.0)
+    code = np.zeros(a.shape, dtype=np.int64)
+    sub = a < 2.0 ** -6                                   # subnormal range: steps of 2^-9
+    code[sub] = np.rint(a[sub] * 2.0 ** 9).astype(np.int64)      # 8 is the smallest normal, as it should be
+    nrm = ~sub
+    frac, exp = np.frexp(a[nrm])                          # a = frac * 2^exp, frac in [0.5, 1)
+    e = exp.astype(np.int64) - 1                          # a = (2 frac) * 2^e, 2 frac in [1, 2)
+    m = np.rint((2.0 * frac - 1.0) * 8.0).astype(np.int64)
+    carry = m == 8
+    e = e + carry
+    m = np.where(carry, 0, m)
+    code[nrm] = np.minimum(((e + 7) << 3) | m, 0x7E)
+    return (code.astype(np.uint8) | sign).astype(np.uint8)
+
+
+def fp8_e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Decode OCP FP8 E4M3 bit patterns (uint8) to float32 exactly (code 0x7F/0xFF -> NaN)."""
+    b = np.ascontiguousarray(b, dtype=np.uint8).astype(np.int64)
+    e, m = (b >> 3) & 15, b & 7
+    mag = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return np.where(b & 0x80, -mag, mag).astype(np.float32)
+
+
+def normal_fp8(seed_seq: np.random.SeedSequence, shape, scale: float = 1.0) -> np.ndarray:
+    """FP8 E4M3 bit patterns of N(0,1) draws divided by ``scale`` (the value a consumer multiplies
+    back in); chunked like normal_bf16, so the result does not depend on the thread count."""
+    n = int(np.prod(shape, dtype=np.int64))
+    out = np.empty(n, dtype=np.uint8)
+    n_chunks = max(1, -(-n // _CHUNK_ELEMS))
+    children = seed_seq.spawn(n_chunks)
+
+    def fill(i):
+        lo = i * _CHUNK_ELEMS
+        hi = min(n, lo + _CHUNK_ELEMS)
+        g = np.random.default_rng(children[i])
+        out[lo:hi] = f32_to_fp8_e4m3_bits(g.standard_normal(hi - lo, dtype=np.float32) / np.float32(scale))
+
+    if n_chunks == 1:
+        fill(0)
+    else:
+        with ThreadPoolExecutor(_GEN_THREADS) as ex:
+            list(ex.map(fill, range(n_chunks)))
+    return out.reshape(shape)
+
+
 @dataclass
 class Geometry:
     num_q_heads: int
     num_kv_heads: int
     head_dim: int
     block_size: int
+    kv_elt_bytes: int = 2          # 2 = bf16 pool, 1 = FP8 E4M3 pool
 
     @property
     def group(self) -> int:
@@ -81,11 +133,11 @@ class Geometry:
 
     @property
     def block_bytes(self) -> int:
-        return 2 * self.block_elems
+        return self.kv_elt_bytes * self.block_elems
 
     @property
     def kv_bytes_per_token(self) -> int:
-        return 2 * self.num_kv_heads * self.head_dim * 2
+        return 2 * self.num_kv_heads * self.head_dim * self.kv_elt_bytes
 
     @property
     def scale(self) -> np.float32:
@@ -174,7 +226,12 @@ def make_decode_case(name, seed, geom: Geometry, context_lens, *, num_blocks=Non
     q = normal_bf16(ss_q, (len(context_lens), geom.num_q_heads, geom.head_dim))
     pool = None
     if materialise_pool:
-        pool = normal_bf16(ss_pool, (num_blocks, 2, geom.num_kv_heads, geom.block_size, geom.head_dim))
+        pshape = (num_blocks, 2, geom.num_kv_heads, geom.block_size, geom.head_dim)
+        if geom.kv_elt_bytes == 1:
+            # K and V are drawn as N(0,1) / scale; the consumer multiplies (k_scale, v_scale) back in
+            pool = normal_fp8(ss_pool, pshape, FP8_KV_SCALE)
+        else:
+            pool = normal_bf16(ss_pool, pshape)
     rng_d = np.random.default_rng(ss_dirty)
     if dirty == "last":
         dirty_ids = np.array([table[b, n - 1] for b, n in enumerate(nb) if n > 0], dtype=np.int32)
@@ -219,8 +276,8 @@ def llama8b_layer(seed=1, shrink=1) -> DecodeCase:
                             dirty="last")
 
 
-def long_context(seed=2, shrink=1, materialise_pool=True) -> DecodeCase:
-    g = Geometry(32, 8, 128, 16)
+def long_context(seed=2, shrink=1, materialise_pool=True, kv_elt_bytes=2) -> DecodeCase:
+    g = Geometry(32, 8, 128, 16, kv_elt_bytes)
     lens = _uniform_lens(seed, 8, 16384 // shrink, 65536 // shrink)
     needed = int(blocks_needed(lens, g.block_size).sum())
     return make_decode_case("long_context", seed, g, lens, max_blocks_per_seq=4096 // shrink,
@@ -274,6 +331,8 @@ class RecoveryCase:
 
 
 REPLICA_CHUNK_BLOCKS = 256
+# FP8 pools hold value / FP8_KV_SCALE; a power of two other than 1 so that a forgotten scale shows
+FP8_KV_SCALE = 0.25
 
 
 def recovery(seed=4, num_blocks=200_000, shrink=1, batch=64) -> RecoveryCase:

@@ -462,3 +462,79 @@ def test_append_rejects_bad_positions_and_ids(oracle):
     with pytest.raises(oracle.OracleError):
         oracle.append_tokens(case.pool.copy(), k_new, v_new, case.block_table, pos, bitmap)
     assert not bitmap.any()
+
+
+# ---- FP8 E4M3 pool -------------------------------------------------------------------------------
+def small_fp8_case(seed=71, lens=(5, 37, 80), Hq=8, Hkv=2, D=64, bs=16, NB=40):
+    g = W.Geometry(Hq, Hkv, D, bs, kv_elt_bytes=1)
+    return W.make_decode_case("small_fp8", seed, g, np.array(lens, np.int32), num_blocks=NB,
+                              max_blocks_per_seq=8, dirty="any", n_dirty=10)
+
+
+def test_fp8_generator_matches_torch_cast_and_exact_fractions():
+    import torch
+    from fractions import Fraction
+    codes = np.arange(256, dtype=np.uint8)
+    dec = W.fp8_e4m3_bits_to_f32(codes)
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    assert np.array_equal(np.isnan(dec), np.isnan(lib)) and np.array_equal(dec[~np.isnan(dec)], lib[~np.isnan(lib)])
+    for c in (0x01, 0x07, 0x08, 0x38, 0x3F, 0x7E, 0xB4):                    # definition, exact rationals
+        e, m = (c >> 3) & 15, c & 7
+        v = Fraction(m, 8) * Fraction(1, 64) if e == 0 else (1 + Fraction(m, 8)) * Fraction(2) ** (e - 7)
+        assert Fraction(float(dec[c])) == (-v if c & 0x80 else v)
+    x = (np.random.default_rng(1).standard_normal(100_000) * 3).astype(np.float32)
+    x = np.concatenate([x, np.float32([0, 2 ** -9, 2 ** -10, 1.5 * 2 ** -9, 2.5 * 2 ** -9, 1.0625, 1.1875, 440, 448])])
+    mine = W.f32_to_fp8_e4m3_bits(x)
+    theirs = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(mine, theirs)
+    assert W.f32_to_fp8_e4m3_bits(np.float32([1000.0, -1e9])).tolist() == [0x7E, 0xFE]     # saturates
+
+
+def test_fp8_decode_matches_torch_sdpa_on_dequantised_values(oracle):
+    import torch
+    case = small_fp8_case()
+    g = case.geom
+    ks, vs = 0.25, 0.5
+    got = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale, k_scale=ks, v_scale=vs)
+    deq = torch.from_numpy(case.pool).view(torch.float8_e4m3fn).to(torch.float64).numpy()   # library decode
+    q = torch.from_numpy(W.bf16_bits_to_f32(case.q).astype(np.float64))
+    for b, L in enumerate(case.context_lens):
+        nb = -(-int(L) // g.block_size)
+        blocks = deq[case.block_table[b, :nb]]
+        k = blocks[:, 0].transpose(0, 2, 1, 3).reshape(-1, g.num_kv_heads, g.head_dim)[:L] * ks
+        v = blocks[:, 1].transpose(0, 2, 1, 3).reshape(-1, g.num_kv_heads, g.head_dim)[:L] * vs
+        kk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(g.group, dim=0)
+        vv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(g.group, dim=0)
+        ref = torch.nn.functional.scaled_dot_product_attention(q[b][:, None, :], kk, vv,
+                                                               scale=float(np.float32(g.scale)))[:, 0]
+        np.testing.assert_allclose(got[b], ref.numpy(), rtol=0, atol=1e-12)
+
+
+def test_fp8_scales_act_as_score_scale_and_output_factor(oracle):
+    case = small_fp8_case(seed=73)
+    g = case.geom
+    base = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale, k_scale=1.0, v_scale=1.0)
+    # v_scale multiplies the output; k_scale is indistinguishable from a change of the softmax scale
+    v2 = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale, k_scale=1.0, v_scale=0.5)
+    np.testing.assert_allclose(v2, 0.5 * base, rtol=1e-15, atol=0)
+    k2 = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale, k_scale=0.5, v_scale=1.0)
+    s2 = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, 0.5 * float(g.scale))
+    np.testing.assert_allclose(k2, s2, rtol=0, atol=1e-13)
+    # single-token context: the output is the stored V code, decoded, times v_scale, exactly
+    one = small_fp8_case(seed=75, lens=(1, 1, 1))
+    got = oracle.decode_attn(one.q, one.pool, one.block_table, one.context_lens, one.geom.scale, k_scale=0.25, v_scale=0.25)
+    v = W.fp8_e4m3_bits_to_f32(one.pool).astype(np.float64) * 0.25
+    for b in range(3):
+        for h in range(one.geom.num_q_heads):
+            assert np.array_equal(got[b, h], v[one.block_table[b, 0], 1, h // one.geom.group, 0])
+
+
+def test_fp8_pack_restore_move_bytes(oracle):
+    case = small_fp8_case(seed=77)
+    ids = case.dirty_ids
+    assert case.geom.block_bytes == case.pool[0].nbytes
+    rep = oracle.pack_blocks(case.pool, ids)
+    assert rep.dtype == np.uint8 and np.array_equal(rep, case.pool[ids])
+    tgt = np.zeros_like(case.pool)
+    oracle.restore_blocks(tgt, rep, ids)
+    assert np.array_equal(tgt[ids], case.pool[ids])
