@@ -357,6 +357,19 @@ def bench_replication_mix(args, kvflow, W):
     }
 
 
+def bench_long_context_fp8(args, kvflow, W):
+    """The timed workload's decode again with an FP8 (E4M3) pool: half the KV bytes per token."""
+    import torch
+    case = W.long_context(kv_elt_bytes=1)
+    pool = kvflow.Fp8Pool(torch.from_numpy(case.pool).cuda(), W.FP8_KV_SCALE, W.FP8_KV_SCALE)
+    dec = Decode(case, pool, kvflow)
+    d = time_calls(dec.run, 50, 10)
+    kv = case.kv_bytes
+    return {"kv_GB": kv / 1e9, "workgroups": dec.workgroups, **d, "kv_GBps": kv / (d["mean_ms"] * 1e-3) / 1e9,
+            "frac_hbm_peak": kv / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "tokens_per_s": float(case.context_lens.sum()) / (d["mean_ms"] * 1e-3)}
+
+
 def bench_llama_layer(args, kvflow, W):
     case = W.llama8b_layer()
     pool = bf16_dev(case.pool)
@@ -407,6 +420,7 @@ def main():
     extra = {
         "timed_workload": {
             "decode": {**d, "kv_GBps": achieved, "frac_hbm_peak": achieved / HBM_PEAK_GBPS,
+                       "tokens_per_s": float(case.context_lens.sum()) / (d["mean_ms"] * 1e-3),
                        "workgroups": main_res["dec"].workgroups},
             "pack": {**main_res["pack"], **copy_rates(main_res["payload"], main_res["pack"]["mean_ms"])},
             "restore": {**main_res["restore"], **copy_rates(main_res["payload"], main_res["restore"]["mean_ms"])},
@@ -434,6 +448,9 @@ def main():
     if not args.only_timed:
         extra["replication_mix"] = bench_replication_mix(args, kvflow, W)
         log("[bench] replication_mix done")
+        torch.cuda.empty_cache()
+        extra["long_context_fp8_pool"] = bench_long_context_fp8(args, kvflow, W)
+        log("[bench] long_context_fp8_pool done")
         torch.cuda.empty_cache()
         extra["llama8b_layer"] = bench_llama_layer(args, kvflow, W)
         log("[bench] llama8b_layer done")

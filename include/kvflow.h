@@ -26,7 +26,8 @@
  *   - pack || decode on two streams is legal (both only read the pool);
  *     restore -> decode needs stream order or an event.
  *
- * Pool layout (bf16): [num_blocks][2][num_kv_heads][block_size][head_dim],
+ * Pool layout: [num_blocks][2][num_kv_heads][block_size][head_dim], elements bf16 or
+ * FP8 E4M3 (half the bytes for every call below; one fp32 scale for K and one for V),
  * second axis 0 = K, 1 = V.  One block is one contiguous chunk of
  * kv_block_bytes() bytes; layers are stacked as separate blocks of one flat pool.
  */
@@ -51,7 +52,7 @@ typedef enum {
     KV_ERR_CONTENT = -7      /* kv_validate_*: a device array violates a precondition */
 } kv_status;
 
-enum { KV_DTYPE_BF16 = 0, KV_DTYPE_F32 = 1 };
+enum { KV_DTYPE_BF16 = 0, KV_DTYPE_F32 = 1, KV_DTYPE_FP8_E4M3 = 2 };
 
 /* Host struct describing the block pool; read during the call only. */
 typedef struct {
@@ -60,10 +61,13 @@ typedef struct {
     int32_t num_kv_heads;  /* > 0 */
     int32_t block_size;    /* tokens per block: 16 or 32 */
     int32_t head_dim;      /* 64 or 128 */
-    int32_t dtype;         /* KV_DTYPE_BF16 */
+    int32_t dtype;         /* KV_DTYPE_BF16, or KV_DTYPE_FP8_E4M3 (OCP 8-bit float, 1-4-3, bias 7) */
+    float   k_scale;       /* FP8 pool only: key value = stored number * k_scale; > 0, finite */
+    float   v_scale;       /* FP8 pool only: value value = stored number * v_scale; > 0, finite */
 } kv_pool_desc;
 
-/* Bytes of one block = 2 * num_kv_heads * block_size * head_dim * 2; 0 if pool is NULL/invalid. */
+/* Bytes of one block = 2 * num_kv_heads * block_size * head_dim * element bytes (2 for bf16, 1 for
+ * FP8); 0 if pool is NULL/invalid. */
 size_t kv_block_bytes(const kv_pool_desc* pool);
 
 /*
@@ -91,7 +95,9 @@ size_t kv_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t num
  * kvh = h / (num_q_heads / num_kv_heads) and L = context_lens[b]:
  *     s[t]   = scale * sum_d q[b,h,d] * K[table[b][t / bs], kvh, t % bs, d]     0 <= t < L
  *     out[b,h,:] = sum_t softmax(s)[t] * V[table[b][t / bs], kvh, t % bs, :]
- * bf16 inputs, fp32 accumulation; L == 0 gives a row of zeros.
+ * bf16 inputs, fp32 accumulation; L == 0 gives a row of zeros.  With an FP8 pool K and V are
+ * the stored numbers times k_scale / v_scale (decoded exactly, products in bf16 x bf16 -> fp32);
+ * q stays bf16.
  *
  *   out            [batch][num_q_heads][head_dim], out_dtype KV_DTYPE_BF16 or KV_DTYPE_F32, written
  *   q              [batch][num_q_heads][head_dim] bf16, read
@@ -150,7 +156,8 @@ int kv_restore_blocks(const kv_pool_desc* pool, const void* replica, const int32
  * kv_append_tokens: one new token per sequence.  For every b with positions[b] >= 0 the rows
  * k_new[b], v_new[b] (all KV heads) are written to position t = positions[b] of sequence b, i.e.
  * row t % bs of block block_table[b][t / bs], and that block's bit is OR-ed into dirty_bitmap.
- *   k_new, v_new   bf16 [batch][num_kv_heads][head_dim], 16-byte aligned, read
+ *   k_new, v_new   [batch][num_kv_heads][head_dim] in the pool's element type (for an FP8 pool:
+ *                  already divided by the scales and rounded), 16-byte aligned, read
  *   positions      int32 [batch], read; < 0 = the sequence takes no token
  *   dirty_bitmap   uint32 [ceil(num_blocks / 32)], bit p % 32 of word p / 32 stands for block p;
  *                  read-modify-written (atomic OR), so it accumulates over steps until collected.

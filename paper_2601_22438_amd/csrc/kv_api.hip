@@ -18,7 +18,10 @@ int check_pool(const kv_pool_desc* pool)
     if (!pool || !pool->base) return KV_ERR_NULL;
     if (pool->num_blocks <= 0 || pool->num_kv_heads <= 0 || pool->block_size <= 0 || pool->head_dim <= 0)
         return KV_ERR_SHAPE;
-    if (pool->dtype != KV_DTYPE_BF16) return KV_ERR_UNSUPPORTED;
+    if (pool->dtype != KV_DTYPE_BF16 && pool->dtype != KV_DTYPE_FP8_E4M3) return KV_ERR_UNSUPPORTED;
+    if (pool->dtype == KV_DTYPE_FP8_E4M3 &&
+        !(pool->k_scale > 0.f && pool->v_scale > 0.f && std::isfinite(pool->k_scale) && std::isfinite(pool->v_scale)))
+        return KV_ERR_SHAPE;
     if (pool->head_dim != 64 && pool->head_dim != 128) return KV_ERR_UNSUPPORTED;
     if (pool->block_size != 16 && pool->block_size != 32) return KV_ERR_UNSUPPORTED;
     if (pool->num_kv_heads > 65535) return KV_ERR_UNSUPPORTED;
@@ -26,9 +29,11 @@ int check_pool(const kv_pool_desc* pool)
     return KV_OK;
 }
 
+size_t elt_bytes_of(const kv_pool_desc* pool) { return pool->dtype == KV_DTYPE_FP8_E4M3 ? 1 : 2; }
+
 size_t block_bytes_of(const kv_pool_desc* pool)
 {
-    return (size_t)2 * pool->num_kv_heads * pool->block_size * pool->head_dim * 2;
+    return (size_t)2 * pool->num_kv_heads * pool->block_size * pool->head_dim * elt_bytes_of(pool);
 }
 
 // Sequences per launch: bounded by the LDS scan and by 32-bit flat tile indices.
@@ -41,14 +46,15 @@ int64_t slice_batch(int32_t num_kv_heads, int32_t max_context_len)
 }
 
 // Persistent workgroups for one launch; 0 on invalid arguments.
-int32_t resolve_workgroups(int32_t batch, int32_t num_kv_heads, int32_t max_context_len, int32_t requested)
+int32_t resolve_workgroups(int32_t batch, int32_t num_kv_heads, int32_t max_context_len, int32_t requested,
+                           int tile_tokens = kTileTokens)
 {
     if (batch <= 0 || num_kv_heads <= 0 || max_context_len < 0 || requested < 0) return 0;
     if (requested > 0) return requested > 65535 ? 0 : requested;
     int64_t bs = slice_batch(num_kv_heads, max_context_len);
     if (bs < 1) return 0;
     if (bs > batch) bs = batch;
-    const int64_t tiles = bs * num_kv_heads * (((int64_t)max_context_len + kTileTokens - 1) / kTileTokens);
+    const int64_t tiles = bs * num_kv_heads * (((int64_t)max_context_len + tile_tokens - 1) / tile_tokens);
     int64_t wg = (tiles + kDecodeWaves * kDecodeMinTilesPerRun - 1) / (kDecodeWaves * kDecodeMinTilesPerRun);
     if (wg < 1) wg = 1;
     if (wg > kDecodeMaxWorkgroups) wg = kDecodeMaxWorkgroups;
@@ -78,6 +84,7 @@ extern "C" {
 size_t kv_block_bytes(const kv_pool_desc* pool)
 {
     if (!pool || pool->num_kv_heads <= 0 || pool->block_size <= 0 || pool->head_dim <= 0) return 0;
+    if (pool->dtype != KV_DTYPE_BF16 && pool->dtype != KV_DTYPE_FP8_E4M3) return 0;
     return block_bytes_of(pool);
 }
 
@@ -121,7 +128,10 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
     if (!aligned16(out) || !aligned16(q)) return KV_ERR_ALIGN;
     const int64_t slice = slice_batch(pool->num_kv_heads, max_context_len);
     if (slice < 1) return KV_ERR_SHAPE;
-    const int32_t wg = resolve_workgroups(batch, pool->num_kv_heads, max_context_len, num_workgroups);
+    const bool fp8 = pool->dtype == KV_DTYPE_FP8_E4M3;
+    // an FP8 pool is scanned in tiles twice as long: never more workgroups than the size query assumed
+    const int32_t wg = resolve_workgroups(batch, pool->num_kv_heads, max_context_len, num_workgroups,
+                                          fp8 ? kFp8TileTokens : kTileTokens);
     const size_t need = kv_decode_workspace_bytes(batch, num_q_heads, pool->num_kv_heads, pool->head_dim,
                                                   max_context_len, num_workgroups);
     if (!workspace || workspace_bytes < need) return KV_ERR_WORKSPACE;
@@ -138,7 +148,8 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
     p.block_size = pool->block_size;
     p.block_shift = pool->block_size == 16 ? 4 : 5;
     p.out_f32 = out_dtype == KV_DTYPE_F32;
-    p.scale_log2e = (float)((double)scale * 1.4426950408889634074);
+    p.scale_log2e = (float)((double)scale * (fp8 ? (double)pool->k_scale : 1.0) * 1.4426950408889634074);
+    p.out_scale = fp8 ? pool->v_scale : 1.f;
     // Slices of the batch run back to back on the stream and reuse the workspace.
     for (int64_t b0 = 0; b0 < batch; b0 += slice) {
         const int64_t nb = batch - b0 < slice ? batch - b0 : slice;
@@ -149,7 +160,8 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
         p.batch = (int32_t)nb;
         p.ws_cum = (int32_t*)workspace;
         p.ws_records = (float*)((char*)workspace + cum_bytes(slice < batch ? slice : batch));
-        hipError_t e = launch_decode(p, D, wg, (hipStream_t)stream);
+        hipError_t e = fp8 ? launch_decode_fp8(p, D, wg, (hipStream_t)stream)
+                           : launch_decode(p, D, wg, (hipStream_t)stream);
         if (e != hipSuccess) return KV_ERR_LAUNCH;
     }
     return KV_OK;
@@ -183,9 +195,10 @@ int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_
     if (batch == 0) return KV_OK;
     if (!k_new || !v_new || !block_table || !positions || !dirty_bitmap) return KV_ERR_NULL;
     if (!aligned16(k_new) || !aligned16(v_new)) return KV_ERR_ALIGN;
-    hipError_t e = launch_append_tokens((uint16_t*)pool->base, (const uint16_t*)k_new, (const uint16_t*)v_new,
-                                        block_table, max_blocks_per_seq, positions, batch, pool->num_kv_heads,
-                                        pool->block_size, pool->head_dim, dirty_bitmap, (hipStream_t)stream);
+    hipError_t e = launch_append_tokens(pool->base, k_new, v_new, block_table, max_blocks_per_seq, positions, batch,
+                                        pool->num_kv_heads, pool->block_size,
+                                        (int)(pool->head_dim * elt_bytes_of(pool)), dirty_bitmap,
+                                        (hipStream_t)stream);
     return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }
 

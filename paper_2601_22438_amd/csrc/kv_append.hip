@@ -20,11 +20,11 @@ constexpr int kAppendThreads = 256;
 constexpr int kCollectThreads = 1024;
 
 __global__ __launch_bounds__(kAppendThreads) void append_tokens_kernel(
-    uint16_t* __restrict__ pool, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+    char* __restrict__ pool, const char* __restrict__ k_new, const char* __restrict__ v_new,
     const int32_t* __restrict__ block_table, int max_blocks_per_seq, const int32_t* __restrict__ positions,
-    int batch, int num_kv_heads, int block_size, int block_shift, int head_dim, uint32_t* __restrict__ dirty_bitmap)
+    int batch, int num_kv_heads, int block_size, int block_shift, int row_bytes, uint32_t* __restrict__ dirty_bitmap)
 {
-    const int chunks_per_row = head_dim / 8;                          // 16-byte chunks in one head's row
+    const int chunks_per_row = row_bytes / 16;                        // 16-byte chunks in one head's row
     const int chunks_per_seq = 2 * num_kv_heads * chunks_per_row;
     const int64_t idx = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;
     if (idx >= (int64_t)batch * chunks_per_seq) return;
@@ -36,8 +36,8 @@ __global__ __launch_bounds__(kAppendThreads) void append_tokens_kernel(
     const int ch = c % chunks_per_row;
     const int64_t p = block_table[(int64_t)b * max_blocks_per_seq + (t >> block_shift)];
     const int r = t & (block_size - 1);
-    const uint16_t* src = (which ? v_new : k_new) + ((int64_t)b * num_kv_heads + kvh) * head_dim + ch * 8;
-    uint16_t* dst = pool + ((((p * 2 + which) * num_kv_heads + kvh) * block_size + r) * (int64_t)head_dim) + ch * 8;
+    const char* src = (which ? v_new : k_new) + ((int64_t)b * num_kv_heads + kvh) * row_bytes + ch * 16;
+    char* dst = pool + ((((p * 2 + which) * num_kv_heads + kvh) * block_size + r) * (int64_t)row_bytes) + ch * 16;
     *(u32x4*)dst = *(const u32x4*)src;
     if (c == 0) atomicOr(dirty_bitmap + (p >> 5), 1u << (p & 31));
 }
@@ -83,17 +83,17 @@ __global__ __launch_bounds__(kCollectThreads) void collect_dirty_kernel(
     }
 }
 
-hipError_t launch_append_tokens(uint16_t* pool, const uint16_t* k_new, const uint16_t* v_new,
+hipError_t launch_append_tokens(void* pool, const void* k_new, const void* v_new,
                                 const int32_t* block_table, int max_blocks_per_seq, const int32_t* positions,
-                                int batch, int num_kv_heads, int block_size, int head_dim,
+                                int batch, int num_kv_heads, int block_size, int row_bytes,
                                 uint32_t* dirty_bitmap, hipStream_t stream)
 {
-    const int64_t threads = (int64_t)batch * 2 * num_kv_heads * (head_dim / 8);
+    const int64_t threads = (int64_t)batch * 2 * num_kv_heads * (row_bytes / 16);
     const int64_t groups = (threads + kAppendThreads - 1) / kAppendThreads;
     if (groups > 0x7FFFFFFF / kAppendThreads) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(append_tokens_kernel, dim3((uint32_t)groups), dim3(kAppendThreads), 0, stream, pool, k_new,
-                       v_new, block_table, max_blocks_per_seq, positions, batch, num_kv_heads, block_size,
-                       block_size == 16 ? 4 : 5, head_dim, dirty_bitmap);
+    hipLaunchKernelGGL(append_tokens_kernel, dim3((uint32_t)groups), dim3(kAppendThreads), 0, stream, (char*)pool,
+                       (const char*)k_new, (const char*)v_new, block_table, max_blocks_per_seq, positions, batch,
+                       num_kv_heads, block_size, block_size == 16 ? 4 : 5, row_bytes, dirty_bitmap);
     return hipGetLastError();
 }
 

@@ -1,0 +1,140 @@
+// Pieces shared by the decode kernels (bf16 pool and FP8 pool): vector types, the split of the
+// flat tile space into runs, and the kernel that merges the per-run records.
+#pragma once
+
+#include "kv_internal.h"
+
+#include <type_traits>
+
+namespace kvflow {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// K/V bytes are used once per decode step: load them with the non-temporal hint so that they
+// stream through the caches instead of displacing each other.
+__device__ __forceinline__ u32x4 stream_load(const uint16_t* p)
+{
+    return __builtin_nontemporal_load((const u32x4*)p);
+}
+
+// The running max of a head only has to be an upper bound of the scores up to a bounded slack
+// (softmax is invariant under the reference point): it is raised, with the cross-lane reduction
+// and the rescale of O that go with it, only when some score of the tile exceeds it by more than
+// this many binary orders of magnitude.  Probabilities then stay below 2^kMaxSlack.
+constexpr float kMaxSlack = 8.f;
+
+// First flat tile of run w when T tiles are dealt to W runs as evenly as possible.
+__device__ __forceinline__ int run_start(int w, int base, int rem) { return w * base + min(w, rem); }
+
+__device__ __forceinline__ int run_of_tile(int t, int base, int rem)
+{
+    const int big = rem * (base + 1);                // tiles held by the runs that got one extra
+    return t < big ? t / (base + 1) : rem + (t - big) / base;
+}
+
+// Combines the records of one (sequence, query head) in a fixed order and normalises.
+// The kernel is latency-bound (cold reads of a few KB per workgroup), so every load of a pass is
+// issued before the first use: the threads are kSlices groups of D/4 lanes, a lane owns 4
+// channels, group s takes runs s, s + kSlices, ... of the pass, and the running max and
+// denominators of the pass go through LDS.  Partial sums of the groups are added in group order.
+// Two sizes: 256 threads when there are few (sequence, head) pairs with many records each, 64
+// when there are thousands of pairs with a handful of records (more workgroups resident at once).
+constexpr int kMergePer = 8;                         // records per thread and pass
+
+template <int D, int kMergeThreads>
+__global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const DecodeParams p, int W)
+{
+    constexpr int kRecord = D + kRecordPad;
+    constexpr int kLanes = D / 4;
+    constexpr int kSlices = kMergeThreads / kLanes;
+    constexpr int kChunk = kSlices * kMergePer;                       // runs per pass (<= 128)
+    __shared__ float sm[kChunk], sl[kChunk];
+    __shared__ __attribute__((aligned(16))) float red[kSlices * D];
+    __shared__ float redl[kSlices];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int Hkv = p.num_kv_heads, G = p.group;
+    const int kvh = h / G, hg = h % G;
+    const int slice = tid / kLanes, c = tid % kLanes;
+    const int64_t out0 = ((int64_t)b * p.num_q_heads + h) * D;
+    const int n = p.ws_cum[b + 1] - p.ws_cum[b];
+    if (n == 0) {                                                     // empty sequence: a row of zeros
+        for (int d = tid; d < D; d += kMergeThreads) {
+            if (p.out_f32) ((float*)p.out)[out0 + d] = 0.f;
+            else ((uint16_t*)p.out)[out0 + d] = 0;
+        }
+        return;
+    }
+    const int T = Hkv * p.ws_cum[p.batch];
+    const int base = T / W, rem = T % W;
+    const int first = Hkv * p.ws_cum[b] + kvh * n;                    // flat range of this row
+    const int w0 = run_of_tile(first, base, rem), w1 = run_of_tile(first + n - 1, base, rem);
+    const int nr = w1 - w0 + 1;
+    const int64_t rec_stride = (int64_t)G * kRecord;               // run w -> run w + 1, same row and head
+    const float* recs = p.ws_records + ((w0 + (int64_t)b * Hkv + kvh) * G + hg) * kRecord;
+
+    float M = -INFINITY, lsum = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < nr; c0 += kChunk) {
+        const int cn = min(kChunk, nr - c0);
+        f32x4 vals[kMergePer];
+#pragma unroll
+        for (int k = 0; k < kMergePer; ++k) {
+            const int i = k * kSlices + slice;
+            vals[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (i < cn) vals[k] = *(const f32x4*)(recs + (c0 + i) * rec_stride + 4 * c);
+        }
+        if (tid < cn) {
+            sm[tid] = recs[(c0 + tid) * rec_stride + D];
+            sl[tid] = recs[(c0 + tid) * rec_stride + D + 1];
+        }
+        __syncthreads();
+        float cm = -INFINITY;
+        for (int i = 0; i < cn; ++i) cm = fmaxf(cm, sm[i]);
+        const float Mn = fmaxf(M, cm);
+        const float a = fast_exp2(M - Mn);
+        M = Mn;
+        acc *= a;
+        lsum *= a;
+#pragma unroll
+        for (int k = 0; k < kMergePer; ++k) {
+            const int i = k * kSlices + slice;
+            if (i < cn) {
+                const float wgt = fast_exp2(sm[i] - Mn);
+                acc += wgt * vals[k];
+                lsum += wgt * sl[i];
+            }
+        }
+        __syncthreads();
+    }
+    *(f32x4*)(red + slice * D + 4 * c) = acc;
+    if (c == 0) redl[slice] = lsum;
+    __syncthreads();
+    for (int d = tid; d < D; d += kMergeThreads) {
+        float o = 0.f, l = 0.f;
+#pragma unroll
+        for (int sidx = 0; sidx < kSlices; ++sidx) { o += red[sidx * D + d]; l += redl[sidx]; }
+        o = o / l * p.out_scale;
+        if (p.out_f32) ((float*)p.out)[out0 + d] = o;
+        else ((__bf16*)p.out)[out0 + d] = (__bf16)o;
+    }
+}
+
+// Launches the merge kernel that fits the number of (sequence, head) pairs.
+template <int D>
+static hipError_t launch_merge(const DecodeParams& p, int workgroups, hipStream_t stream)
+{
+    const dim3 mgrid((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1);
+    if ((int64_t)p.batch * p.num_q_heads >= 2048)
+        hipLaunchKernelGGL((decode_merge_kernel<D, 64>), mgrid, dim3(64), 0, stream, p, workgroups * kDecodeWaves);
+    else
+        hipLaunchKernelGGL((decode_merge_kernel<D, 256>), mgrid, dim3(256), 0, stream, p, workgroups * kDecodeWaves);
+    return hipGetLastError();
+}
+
+}  // namespace kvflow

@@ -35,19 +35,24 @@ struct DecodeParams {
     int32_t batch, num_q_heads, num_kv_heads, group;
     int32_t block_size, block_shift;
     int32_t out_f32;
-    float scale_log2e;         // scale * log2(e)
+    float scale_log2e;         // scale * log2(e), times the K scale of an FP8 pool
+    float out_scale;           // 1, or the V scale of an FP8 pool (applied by the merge kernel)
 };
 
 hipError_t launch_decode(const DecodeParams& p, int head_dim, int workgroups, hipStream_t stream);
+// FP8 (E4M3) pool: p.pool points at bytes; tiles are kFp8TileTokens tokens.
+hipError_t launch_decode_fp8(const DecodeParams& p, int head_dim, int workgroups, hipStream_t stream);
+constexpr int kFp8TileTokens = 64;
 
 // dst/src are the replica and the pool; to_replica selects the direction.  count (device, may be
 // NULL) limits the list to its first *count entries; n then is the launch bound.
 hipError_t launch_copy_blocks(void* replica, void* pool, size_t block_bytes, const int32_t* block_ids,
                               int64_t n, const int32_t* count, bool to_replica, hipStream_t stream);
 
-hipError_t launch_append_tokens(uint16_t* pool, const uint16_t* k_new, const uint16_t* v_new,
+// row_bytes = head_dim * element size (a multiple of 16).
+hipError_t launch_append_tokens(void* pool, const void* k_new, const void* v_new,
                                 const int32_t* block_table, int max_blocks_per_seq, const int32_t* positions,
-                                int batch, int num_kv_heads, int block_size, int head_dim,
+                                int batch, int num_kv_heads, int block_size, int row_bytes,
                                 uint32_t* dirty_bitmap, hipStream_t stream);
 
 hipError_t launch_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* ids_out, int64_t capacity,

@@ -14,6 +14,7 @@ import torch
 
 KV_DTYPE_BF16 = 0
 KV_DTYPE_F32 = 1
+KV_DTYPE_FP8_E4M3 = 2
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvflow.so")
 _lib = None
@@ -28,7 +29,8 @@ class KvflowError(RuntimeError):
 class kv_pool_desc(ctypes.Structure):
     _fields_ = [("base", ctypes.c_void_p), ("num_blocks", ctypes.c_int64),
                 ("num_kv_heads", ctypes.c_int32), ("block_size", ctypes.c_int32),
-                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float)]
 
 
 def lib_path() -> str:
@@ -90,17 +92,33 @@ def _ptr(t) -> int:
     return 0 if t is None else int(t.data_ptr())
 
 
-def pool_desc(pool: torch.Tensor) -> kv_pool_desc:
-    """Describe a pool tensor of shape [NB][2][Hkv][bs][D] (bf16, contiguous, on the GPU)."""
-    if pool.dim() != 5 or pool.shape[1] != 2 or not pool.is_contiguous():
+class Fp8Pool:
+    """An FP8 E4M3 pool: a contiguous uint8 (or float8_e4m3fn) tensor [NB][2][Hkv][bs][D] plus its scales."""
+
+    def __init__(self, data: torch.Tensor, k_scale: float, v_scale: float):
+        if data.element_size() != 1:
+            raise ValueError("FP8 pool data must have 1-byte elements")
+        self.data, self.k_scale, self.v_scale = data, float(k_scale), float(v_scale)
+
+    @property
+    def shape(self):
+        return self.data.shape
+
+
+def pool_desc(pool) -> kv_pool_desc:
+    """Describe a pool of shape [NB][2][Hkv][bs][D]: a bf16 tensor, or an Fp8Pool (contiguous, on the GPU)."""
+    data = pool.data if isinstance(pool, Fp8Pool) else pool
+    if data.dim() != 5 or data.shape[1] != 2 or not data.is_contiguous():
         raise ValueError("pool must be a contiguous [NB][2][Hkv][bs][D] tensor")
-    if pool.dtype != torch.bfloat16:
-        raise ValueError("pool must be bfloat16")
-    nb, _, hkv, bs, d = pool.shape
-    return kv_pool_desc(pool.data_ptr(), nb, hkv, bs, d, KV_DTYPE_BF16)
+    nb, _, hkv, bs, d = data.shape
+    if isinstance(pool, Fp8Pool):
+        return kv_pool_desc(data.data_ptr(), nb, hkv, bs, d, KV_DTYPE_FP8_E4M3, pool.k_scale, pool.v_scale)
+    if data.dtype != torch.bfloat16:
+        raise ValueError("pool must be bfloat16 (or wrapped in Fp8Pool)")
+    return kv_pool_desc(data.data_ptr(), nb, hkv, bs, d, KV_DTYPE_BF16, 1.0, 1.0)
 
 
-def kv_block_bytes(pool: torch.Tensor) -> int:
+def kv_block_bytes(pool) -> int:
     return int(load().kv_block_bytes(ctypes.byref(pool_desc(pool))))
 
 

@@ -18,13 +18,29 @@ def bits_of(t: torch.Tensor) -> np.ndarray:
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+def pool_tensor(bits, k_scale=1.0, v_scale=1.0):
+    """Pool bit patterns -> what the binding takes: a bf16 tensor, or an Fp8Pool for uint8 patterns."""
+    if bits.dtype == np.uint8:
+        return kvflow.Fp8Pool(torch.from_numpy(np.ascontiguousarray(bits)).cuda(), k_scale, v_scale)
+    return bf16_tensor(bits)
+
+
+def pool_bits_of(pool) -> np.ndarray:
+    if isinstance(pool, kvflow.Fp8Pool):
+        return pool.data.cpu().numpy()
+    return bits_of(pool)
+
+
 class DeviceCase:
-    def __init__(self, case, pool_bits=None):
+    def __init__(self, case, pool_bits=None, k_scale=1.0, v_scale=1.0):
         self.case = case
         g = case.geom
         self.q = bf16_tensor(case.q)
         pool_bits = case.pool if pool_bits is None else pool_bits
-        self.pool = bf16_tensor(pool_bits) if not torch.is_tensor(pool_bits) else pool_bits
+        if torch.is_tensor(pool_bits) or isinstance(pool_bits, kvflow.Fp8Pool):
+            self.pool = pool_bits
+        else:
+            self.pool = pool_tensor(pool_bits, k_scale, v_scale)
         self.block_table = torch.from_numpy(case.block_table).cuda()
         self.context_lens = torch.from_numpy(case.context_lens).cuda()
         self.max_len = case.max_context_len

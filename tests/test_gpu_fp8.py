@@ -1,0 +1,132 @@
+"""GPU parity with an FP8 (E4M3) block pool: the oracle consumes the same bit patterns, so the
+tolerance is that of the arithmetic only (max-abs 2e-2, mean-abs 2e-3); copies are bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_22438_amd import kvflow
+from paper_2601_22438_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import DeviceCase, assert_close_to_oracle, pool_bits_of, pool_tensor  # noqa: E402
+
+KS, VS = W.FP8_KV_SCALE, W.FP8_KV_SCALE
+
+
+def make(seed, Hq, Hkv, D, bs, lens, NB=None, MB=None, dirty="last", n_dirty=None):
+    g = W.Geometry(Hq, Hkv, D, bs, kv_elt_bytes=1)
+    return W.make_decode_case("t8", seed, g, np.asarray(lens, np.int32), num_blocks=NB,
+                              max_blocks_per_seq=MB, dirty=dirty, n_dirty=n_dirty)
+
+
+def oracle_decode(oracle, case, pool=None, table=None, rows=None, ks=KS, vs=VS):
+    return oracle.decode_attn(case.q, case.pool if pool is None else pool,
+                              case.block_table if table is None else table, case.context_lens,
+                              case.geom.scale, rows=rows, k_scale=ks, v_scale=vs)
+
+
+GEOMS = [(8, 2, 64, 16), (32, 8, 128, 16), (64, 8, 128, 32), (4, 4, 128, 16), (16, 1, 64, 32), (6, 3, 64, 16)]
+RAGGED = [1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 79, 80, 81, 127, 128, 129, 200, 257, 300]
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("wgs", [0, 1, 3, 64])
+def test_fp8_decode_ragged_lengths_and_grid_sizes(oracle, geom, wgs):
+    Hq, Hkv, D, bs = geom
+    case = make(501, Hq, Hkv, D, bs, RAGGED, MB=-(-300 // bs))
+    want = oracle_decode(oracle, case)
+    dc = DeviceCase(case, k_scale=KS, v_scale=VS)
+    for dt in (torch.float32, torch.bfloat16):
+        assert_close_to_oracle(dc.decode(dt, workgroups=wgs), want, f"fp8 {geom} workgroups={wgs} {dt}")
+
+
+def test_fp8_scales_are_applied(oracle):
+    case = make(503, 32, 8, 128, 16, [100, 333, 64], MB=24)
+    # stored numbers are N(0,1) / 0.25: scales near 0.25 keep values O(1), where the absolute tolerance is meant
+    for ks, vs in ((0.25, 0.25), (0.125, 0.25), (0.5, 0.0625), (0.25, 0.125)):
+        dc = DeviceCase(case, k_scale=ks, v_scale=vs)
+        assert_close_to_oracle(dc.decode(torch.float32), oracle_decode(oracle, case, ks=ks, vs=vs), f"scales {ks} {vs}")
+
+
+def test_fp8_single_token_returns_decoded_v_times_scale_exactly(oracle):
+    case = make(505, 32, 8, 128, 16, [1] * 5, MB=4)
+    want = oracle_decode(oracle, case)                       # = decoded V code * v_scale, pinned on the CPU
+    got = DeviceCase(case, k_scale=KS, v_scale=VS).decode(torch.float32).to(torch.float64).cpu().numpy()
+    assert np.array_equal(got, want)
+
+
+def test_fp8_zero_length_poison_and_permutation(oracle):
+    case = make(507, 32, 8, 128, 16, [0, 37, 130, 5, 0, 64], MB=12)
+    g = case.geom
+    want = oracle_decode(oracle, case)
+    pool = np.full_like(case.pool, 0x7F)                     # NaN code everywhere ...
+    for b, L in enumerate(case.context_lens):
+        for jb in range(-(-int(L) // g.block_size)):
+            valid = min(g.block_size, int(L) - jb * g.block_size)
+            pid = case.block_table[b, jb]
+            pool[pid, :, :, :valid] = case.pool[pid, :, :, :valid]      # ... except the valid rows
+    dc = DeviceCase(case, pool_bits=pool, k_scale=KS, v_scale=VS)
+    a = dc.decode(torch.float32)
+    assert_close_to_oracle(a, want, "fp8 poisoned")
+    assert torch.count_nonzero(a[0]) == 0 and torch.count_nonzero(a[4]) == 0
+    perm = np.random.default_rng(3).permutation(case.num_blocks)
+    pool2 = np.empty_like(pool)
+    pool2[perm] = pool
+    table2 = np.where(case.block_table >= 0, perm[np.maximum(case.block_table, 0)], -1).astype(np.int32)
+    b = dc.decode(torch.float32, pool=pool_tensor(pool2, KS, VS), block_table=torch.from_numpy(table2).cuda())
+    assert torch.equal(a, b)
+
+
+def test_fp8_pack_restore_and_append_bitwise(oracle):
+    case = make(509, 64, 8, 128, 32, [40, 100, 7, 64], NB=60, MB=6, dirty="any", n_dirty=21)
+    pool = pool_tensor(case.pool, KS, VS)
+    assert kvflow.kv_block_bytes(pool) == case.geom.block_bytes == case.pool[0].nbytes
+    ids = torch.from_numpy(case.dirty_ids).cuda()
+    replica = torch.zeros((len(case.dirty_ids),) + tuple(case.pool.shape[1:]), dtype=torch.uint8, device="cuda")
+    kvflow.kv_pack_blocks(replica, pool, ids)
+    torch.cuda.synchronize()
+    want = oracle.pack_blocks(case.pool, case.dirty_ids)
+    assert np.array_equal(replica.cpu().numpy(), want)
+    fresh = np.random.default_rng(2).permutation(case.num_blocks)[:len(case.dirty_ids)].astype(np.int32)
+    tgt_bits = W.normal_fp8(np.random.SeedSequence(9), case.pool.shape)
+    target = pool_tensor(tgt_bits, KS, VS)
+    kvflow.kv_restore_blocks(target, replica, torch.from_numpy(fresh).cuda())
+    torch.cuda.synchronize()
+    oracle.restore_blocks(tgt_bits, want, fresh)
+    assert np.array_equal(pool_bits_of(target), tgt_bits)
+    # append one token per sequence (positions inside the last, partly filled block)
+    g = case.geom
+    ss = np.random.SeedSequence(11).spawn(2)
+    k_new = W.normal_fp8(ss[0], (case.batch, g.num_kv_heads, g.head_dim), KS)
+    v_new = W.normal_fp8(ss[1], (case.batch, g.num_kv_heads, g.head_dim), VS)
+    pos = case.context_lens.copy()
+    pos[3] = -1                                              # its block is full and the table has no next one
+    host = case.pool.copy().view(np.uint8)
+    # the oracle's append moves 16-bit elements; an FP8 row is moved as head_dim/2 of them
+    pool16 = host.reshape(case.num_blocks, 2, g.num_kv_heads, g.block_size, g.head_dim // 2, 2).view(np.uint16)[..., 0]
+    pool16 = np.ascontiguousarray(pool16)
+    bm_h = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    oracle.append_tokens(pool16, k_new.view(np.uint16).reshape(case.batch, g.num_kv_heads, -1),
+                         v_new.view(np.uint16).reshape(case.batch, g.num_kv_heads, -1), case.block_table, pos, bm_h)
+    bm_d = torch.zeros(len(bm_h), dtype=torch.int32, device="cuda")
+    kvflow.kv_append_tokens(pool, torch.from_numpy(k_new).cuda(), torch.from_numpy(v_new).cuda(),
+                            torch.from_numpy(case.block_table).cuda(), torch.from_numpy(pos).cuda(), bm_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(pool_bits_of(pool).view(np.uint16).reshape(pool16.shape), pool16)
+    assert np.array_equal(bm_d.cpu().numpy().view(np.uint32), bm_h)
+
+
+def test_fp8_long_context_sampled_rows(oracle):
+    case = W.long_context(kv_elt_bytes=1)
+    g = case.geom
+    assert case.kv_bytes == int(case.context_lens.sum()) * 2 * g.num_kv_heads * g.head_dim
+    dc = DeviceCase(case, k_scale=KS, v_scale=VS)
+    rng = np.random.default_rng(5)
+    flat = rng.choice(case.batch * g.num_q_heads, size=20, replace=False)
+    rows = np.stack([flat // g.num_q_heads, flat % g.num_q_heads], axis=1).astype(np.int32)
+    want = oracle_decode(oracle, case, rows=rows)
+    for dt in (torch.bfloat16, torch.float32):
+        got = dc.decode(dt)
+        sub = got[torch.from_numpy(rows[:, 0]).long().cuda(), torch.from_numpy(rows[:, 1]).long().cuda()]
+        assert_close_to_oracle(sub, want, f"fp8 long_context {dt}")

@@ -43,7 +43,7 @@ def test_binding_has_the_same_names():
 
 
 def desc(kvflow, base=0x10000, nb=8, hkv=2, bs=16, d=64, dtype=0):
-    return kvflow.kv_pool_desc(base, nb, hkv, bs, d, dtype)
+    return kvflow.kv_pool_desc(base, nb, hkv, bs, d, dtype, 1.0, 1.0)
 
 
 def decode(lib, kvflow, pool, out=0x20000, q=0x30000, table=0x40000, lens=0x50000, mb=4, batch=2, hq=8,
