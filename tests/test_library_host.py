@@ -139,3 +139,14 @@ def test_append_collect_counted_pack_reject_bad_arguments(lib):
     assert pc(n=0) == 0
     assert pc(cnt=0) == -1 and pc(rep=0) == -1 and pc(ids=0) == -1
     assert pc(n=-2) == -2
+
+
+def test_fp8_pool_descriptor_checks(lib):
+    from paper_2601_22438_amd import kvflow
+    fp8 = lambda ks=0.25, vs=0.5, **kw: kvflow.kv_pool_desc(kw.get("base", 0x10000), 8, 8, 16, 128, 2, ks, vs)
+    assert lib.kv_block_bytes(ctypes.byref(fp8())) == 32768                     # half of the bf16 block
+    assert decode(lib, kvflow, fp8(), hq=32, batch=0) == 0
+    for bad in (fp8(ks=0.0), fp8(vs=-1.0), fp8(ks=float("inf")), fp8(vs=float("nan"))):
+        assert decode(lib, kvflow, bad, hq=32) == -2
+    assert decode(lib, kvflow, kvflow.kv_pool_desc(0x10000, 8, 8, 16, 128, 3, 1.0, 1.0), hq=32) == -3
+    assert lib.kv_block_bytes(ctypes.byref(kvflow.kv_pool_desc(0x10000, 8, 8, 16, 128, 3, 1.0, 1.0))) == 0
