@@ -292,7 +292,12 @@ def bench_replication_mix(args, kvflow, W):
     a_t = time_calls(lambda: kvflow.kv_append_tokens(pool, k_new, v_new, dec.table, positions, bitmap), 20, 5)
     c_t = time_calls(lambda: kvflow.kv_collect_dirty(bitmap, case.num_blocks, ids_dev, cnt_dev, False), 20, 5)
     p_t = time_calls(lambda: kvflow.kv_pack_blocks_counted(replica, pool, ids_dev, cnt_dev), 20, 5)
-    loop = {"append_us": a_t["mean_ms"] * 1e3, "collect_dirty_us": c_t["mean_ms"] * 1e3,
+    k_out, v_out = torch.empty_like(k_new), torch.empty_like(v_new)
+    g_t = time_calls(lambda: kvflow.kv_gather_tokens(k_out, v_out, pool, dec.table, positions), 20, 5)
+    loop = {"gather_tokens_us": g_t["mean_ms"] * 1e3,
+            "bytes_per_step_block_granular": n * g.block_bytes,
+            "bytes_per_step_token_granular": case.batch * g.kv_bytes_per_token,
+            "append_us": a_t["mean_ms"] * 1e3, "collect_dirty_us": c_t["mean_ms"] * 1e3,
             "pack_counted_us": p_t["mean_ms"] * 1e3, "dirty_found": int(cnt_dev.item()),
             "note": "latency-bound helpers (KB to MB of traffic); times include launch and event overhead"}
     # pack into pinned host memory (a transport buffer on the far side of PCIe): rate, and what a

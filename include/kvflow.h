@@ -170,6 +170,18 @@ int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_
                      int32_t batch, uint32_t* dirty_bitmap, void* stream);
 
 /*
+ * kv_gather_tokens: the inverse of kv_append_tokens, for replication at token granularity (what
+ * a step has written is one row per sequence, not the block around it; over a slow link the
+ * difference is a factor of block_size).  For every b with positions[b] >= 0 the K and V rows at
+ * position positions[b] of sequence b are copied to k_out[b], v_out[b]; other rows of k_out, v_out
+ * are left untouched.  The replication target applies the received rows with kv_append_tokens.
+ *   k_out, v_out   [batch][num_kv_heads][head_dim] in the pool's element type, 16-byte aligned, written
+ * Preconditions as for kv_append_tokens.
+ */
+int kv_gather_tokens(void* k_out, void* v_out, const kv_pool_desc* pool, const int32_t* block_table,
+                     int32_t max_blocks_per_seq, const int32_t* positions, int32_t batch, void* stream);
+
+/*
  * kv_collect_dirty: dirty bitmap -> ascending list of block ids, on the device.
  *   dirty_ids    int32 [capacity], written: the first min(count, capacity) dirty ids, ascending
  *   dirty_count  int32 [1], written: the number of dirty blocks (may exceed capacity: the caller

@@ -10,6 +10,7 @@ from .kv_oracle import (  # noqa: F401
     build,
     collect_dirty,
     decode_attn,
+    gather_tokens,
     pack_blocks,
     restore_blocks,
 )

@@ -273,3 +273,37 @@ int64_t kvo_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* i
     if (clear) for (int64_t w = 0; w < (num_blocks + 31) / 32; ++w) dirty_bitmap[w] = 0;
     return n;
 }
+
+/*
+ * Token-granular replication, gather side: the rows of the tokens at positions[b] (the ones a
+ * step has just written) are copied out of the pool into contiguous arrays
+ * k_out, v_out [batch][num_kv_heads][row_elems]; the inverse of kvo_append_tokens, which is what
+ * the replication target runs on the received rows.  Rows of sequences with positions[b] < 0
+ * are left untouched.  Elements are 16-bit; an FP8 row is passed as head_dim / 2 of them.
+ */
+int kvo_gather_tokens(const uint16_t* pool, int64_t num_blocks, int num_kv_heads, int block_size, int row_elems,
+                      uint16_t* k_out, uint16_t* v_out, const int32_t* block_table, int max_blocks_per_seq,
+                      const int32_t* positions, int batch)
+{
+    if (num_blocks <= 0 || num_kv_heads <= 0 || block_size <= 0 || row_elems <= 0 || batch < 0) return -2;
+    for (int b = 0; b < batch; ++b) {
+        int t = positions[b];
+        if (t < 0) continue;
+        if ((int64_t)t >= (int64_t)max_blocks_per_seq * block_size) return -3;
+        int32_t p = block_table[(int64_t)b * max_blocks_per_seq + t / block_size];
+        if (p < 0 || p >= num_blocks) return -4;
+    }
+    for (int b = 0; b < batch; ++b) {
+        int t = positions[b];
+        if (t < 0) continue;
+        int64_t p = block_table[(int64_t)b * max_blocks_per_seq + t / block_size];
+        int r = t % block_size;
+        for (int kvh = 0; kvh < num_kv_heads; ++kvh)
+            for (int which = 0; which < 2; ++which) {
+                const uint16_t* src = pool + ((((p * 2 + which) * num_kv_heads + kvh) * block_size + r) * (int64_t)row_elems);
+                uint16_t* dst = (which ? v_out : k_out) + ((int64_t)b * num_kv_heads + kvh) * row_elems;
+                for (int d = 0; d < row_elems; ++d) dst[d] = src[d];
+            }
+    }
+    return 0;
+}

@@ -62,6 +62,9 @@ def _load():
         lib.kvo_append_tokens.restype = ctypes.c_int
         lib.kvo_append_tokens.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                           u16p, u16p, i32p, ctypes.c_int, i32p, ctypes.c_int, u32p]
+        lib.kvo_gather_tokens.restype = ctypes.c_int
+        lib.kvo_gather_tokens.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                          u16p, u16p, i32p, ctypes.c_int, i32p, ctypes.c_int]
         lib.kvo_collect_dirty.restype = ctypes.c_int64
         lib.kvo_collect_dirty.argtypes = [u32p, ctypes.c_int64, i32p, ctypes.c_int]
         for fn in (lib.kvo_pack_blocks, lib.kvo_restore_blocks):
@@ -200,3 +203,20 @@ def collect_dirty(dirty_bitmap, num_blocks, clear=True):
     n = _load().kvo_collect_dirty(_ptr(dirty_bitmap, ctypes.c_uint32), int(num_blocks),
                                   _ptr(ids, ctypes.c_int32), int(bool(clear)))
     return ids[:n].copy()
+
+
+def gather_tokens(pool, block_table, positions, k_out=None, v_out=None):
+    """Copy the K/V rows of the tokens at positions[b] out of the pool: returns (k, v), each uint16
+    [B][Hkv][D]; rows of sequences with positions[b] < 0 keep what k_out / v_out held (zeros by default)."""
+    pool = _c(pool, np.uint16)
+    block_table, positions = _c(block_table, np.int32), _c(positions, np.int32)
+    NB, two, Hkv, bs, D = pool.shape
+    B = len(positions)
+    k_out = np.zeros((B, Hkv, D), np.uint16) if k_out is None else k_out
+    v_out = np.zeros((B, Hkv, D), np.uint16) if v_out is None else v_out
+    if k_out.shape != (B, Hkv, D) or v_out.shape != (B, Hkv, D) or block_table.shape[0] != B:
+        raise OracleError("inconsistent shapes")
+    _check(_load().kvo_gather_tokens(
+        _ptr(pool, ctypes.c_uint16), NB, Hkv, bs, D, _ptr(k_out, ctypes.c_uint16), _ptr(v_out, ctypes.c_uint16),
+        _ptr(block_table, ctypes.c_int32), block_table.shape[1], _ptr(positions, ctypes.c_int32), B))
+    return k_out, v_out

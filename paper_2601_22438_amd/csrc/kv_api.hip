@@ -202,6 +202,21 @@ int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_
     return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }
 
+int kv_gather_tokens(void* k_out, void* v_out, const kv_pool_desc* pool, const int32_t* block_table,
+                     int32_t max_blocks_per_seq, const int32_t* positions, int32_t batch, void* stream)
+{
+    int rc = check_pool(pool);
+    if (rc != KV_OK) return rc;
+    if (batch < 0 || max_blocks_per_seq <= 0) return KV_ERR_SHAPE;
+    if (batch == 0) return KV_OK;
+    if (!k_out || !v_out || !block_table || !positions) return KV_ERR_NULL;
+    if (!aligned16(k_out) || !aligned16(v_out)) return KV_ERR_ALIGN;
+    hipError_t e = launch_gather_tokens(pool->base, k_out, v_out, block_table, max_blocks_per_seq, positions, batch,
+                                        pool->num_kv_heads, pool->block_size,
+                                        (int)(pool->head_dim * elt_bytes_of(pool)), (hipStream_t)stream);
+    return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
+}
+
 int kv_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* dirty_ids, int64_t capacity,
                      int32_t* dirty_count, int32_t clear, void* stream)
 {

@@ -42,6 +42,30 @@ __global__ __launch_bounds__(kAppendThreads) void append_tokens_kernel(
     if (c == 0) atomicOr(dirty_bitmap + (p >> 5), 1u << (p & 31));
 }
 
+// The inverse direction for token-granular replication: the rows at positions[b] leave the pool
+// for contiguous arrays (what travels is the new token, not the block around it).
+__global__ __launch_bounds__(kAppendThreads) void gather_tokens_kernel(
+    const char* __restrict__ pool, char* __restrict__ k_out, char* __restrict__ v_out,
+    const int32_t* __restrict__ block_table, int max_blocks_per_seq, const int32_t* __restrict__ positions,
+    int batch, int num_kv_heads, int block_size, int block_shift, int row_bytes)
+{
+    const int chunks_per_row = row_bytes / 16;
+    const int chunks_per_seq = 2 * num_kv_heads * chunks_per_row;
+    const int64_t idx = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;
+    if (idx >= (int64_t)batch * chunks_per_seq) return;
+    const int b = (int)(idx / chunks_per_seq), c = (int)(idx % chunks_per_seq);
+    const int t = positions[b];
+    if (t < 0) return;
+    const int which = c / (num_kv_heads * chunks_per_row);
+    const int kvh = (c / chunks_per_row) % num_kv_heads;
+    const int ch = c % chunks_per_row;
+    const int64_t p = block_table[(int64_t)b * max_blocks_per_seq + (t >> block_shift)];
+    const int r = t & (block_size - 1);
+    const char* src = pool + ((((p * 2 + which) * num_kv_heads + kvh) * block_size + r) * (int64_t)row_bytes) + ch * 16;
+    char* dst = (which ? v_out : k_out) + ((int64_t)b * num_kv_heads + kvh) * row_bytes + ch * 16;
+    *(u32x4*)dst = *(const u32x4*)src;
+}
+
 __global__ __launch_bounds__(kCollectThreads) void collect_dirty_kernel(
     uint32_t* __restrict__ dirty_bitmap, int64_t num_blocks, int32_t* __restrict__ ids_out, int64_t capacity,
     int32_t* __restrict__ count_out, int clear)
@@ -94,6 +118,19 @@ hipError_t launch_append_tokens(void* pool, const void* k_new, const void* v_new
     hipLaunchKernelGGL(append_tokens_kernel, dim3((uint32_t)groups), dim3(kAppendThreads), 0, stream, (char*)pool,
                        (const char*)k_new, (const char*)v_new, block_table, max_blocks_per_seq, positions, batch,
                        num_kv_heads, block_size, block_size == 16 ? 4 : 5, row_bytes, dirty_bitmap);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_tokens(const void* pool, void* k_out, void* v_out, const int32_t* block_table,
+                                int max_blocks_per_seq, const int32_t* positions, int batch, int num_kv_heads,
+                                int block_size, int row_bytes, hipStream_t stream)
+{
+    const int64_t threads = (int64_t)batch * 2 * num_kv_heads * (row_bytes / 16);
+    const int64_t groups = (threads + kAppendThreads - 1) / kAppendThreads;
+    if (groups > 0x7FFFFFFF / kAppendThreads) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gather_tokens_kernel, dim3((uint32_t)groups), dim3(kAppendThreads), 0, stream,
+                       (const char*)pool, (char*)k_out, (char*)v_out, block_table, max_blocks_per_seq, positions,
+                       batch, num_kv_heads, block_size, block_size == 16 ? 4 : 5, row_bytes);
     return hipGetLastError();
 }
 

@@ -62,6 +62,8 @@ def load() -> ctypes.CDLL:
     lib.kv_pack_blocks_counted.argtypes = [P, PD, P, P, I64, P]
     lib.kv_append_tokens.restype = ctypes.c_int
     lib.kv_append_tokens.argtypes = [PD, P, P, P, I32, P, I32, P, P]
+    lib.kv_gather_tokens.restype = ctypes.c_int
+    lib.kv_gather_tokens.argtypes = [P, P, PD, P, I32, P, I32, P]
     lib.kv_collect_dirty.restype = ctypes.c_int
     lib.kv_collect_dirty.argtypes = [P, I64, P, I64, P, I32, P]
     lib.kv_validate_decode.restype = ctypes.c_int
@@ -170,6 +172,12 @@ def kv_append_tokens(pool, k_new, v_new, block_table, positions, dirty_bitmap, s
     _check(load().kv_append_tokens(ctypes.byref(pool_desc(pool)), _ptr(k_new), _ptr(v_new), _ptr(block_table),
                                    block_table.shape[1], _ptr(positions), positions.numel(),
                                    _ptr(dirty_bitmap), _stream_handle(stream)))
+
+
+def kv_gather_tokens(k_out, v_out, pool, block_table, positions, stream=None) -> None:
+    """Enqueue the copy of the K/V rows at positions[b] out of the pool into k_out[b], v_out[b]."""
+    _check(load().kv_gather_tokens(_ptr(k_out), _ptr(v_out), ctypes.byref(pool_desc(pool)), _ptr(block_table),
+                                   block_table.shape[1], _ptr(positions), positions.numel(), _stream_handle(stream)))
 
 
 def kv_collect_dirty(dirty_bitmap, num_blocks, dirty_ids, dirty_count, clear=True, stream=None) -> None:

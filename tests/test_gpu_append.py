@@ -132,3 +132,33 @@ def test_replication_loop_on_device(oracle):
     b = DeviceCase(case, pool_bits=target).decode(torch.bfloat16)
     assert torch.equal(a, b)
     assert_close_to_oracle(b, oracle.decode_attn(case.q, pool_h, case.block_table, lens, g.scale), "target decode")
+
+
+@pytest.mark.parametrize("geom", [(8, 2, 64, 16), (64, 8, 128, 32)])
+def test_gather_tokens_and_token_granular_replication(oracle, geom):
+    Hq, Hkv, D, bs = geom
+    case = case_with_room(205, Hq, Hkv, D, bs, [3, 16, 31, 100, 255, 64], 1)
+    g = case.geom
+    table_d = torch.from_numpy(case.block_table).cuda()
+    src = bf16_tensor(case.pool)
+    target = src.clone()                                            # the target holds the state before the step
+    k_new, v_new = new_tokens(case, 500)
+    pos = case.context_lens.copy()
+    pos[2] = -1
+    pos_d = torch.from_numpy(pos).cuda()
+    bm = torch.zeros(oracle.bitmap_words(case.num_blocks), dtype=torch.int32, device="cuda")
+    kvflow.kv_append_tokens(src, bf16_tensor(k_new), bf16_tensor(v_new), table_d, pos_d, bm)
+    # what travels: the new rows only
+    k_out = torch.full((case.batch, g.num_kv_heads, g.head_dim), 7.0, dtype=torch.bfloat16, device="cuda")
+    v_out = torch.full_like(k_out, 7.0)
+    kvflow.kv_gather_tokens(k_out, v_out, src, table_d, pos_d)
+    torch.cuda.synchronize()
+    pool_h = case.pool.copy()
+    oracle.append_tokens(pool_h, k_new, v_new, case.block_table, pos, np.zeros(len(bm), np.uint32))
+    seven = bits_of(torch.full((1,), 7.0, dtype=torch.bfloat16))[0]
+    want_k, want_v = oracle.gather_tokens(pool_h, case.block_table, pos,
+                                          np.full(k_new.shape, seven, np.uint16), np.full(k_new.shape, seven, np.uint16))
+    assert np.array_equal(bits_of(k_out), want_k) and np.array_equal(bits_of(v_out), want_v)
+    kvflow.kv_append_tokens(target, k_out, v_out, table_d, pos_d, bm)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(target), pool_h) and np.array_equal(bits_of(src), pool_h)

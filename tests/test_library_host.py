@@ -130,6 +130,11 @@ def test_append_collect_counted_pack_reject_bad_arguments(lib):
     assert ap(b=-1) == -2 and ap(mb=0) == -2
     assert ap(p=desc(kvflow, d=48)) == -3
     assert ap(k=0x20008) == -4
+    ga = lambda k=0x20000, v=0x30000, tb=0x40000, mb=4, pos=0x50000, b=2: \
+        lib.kv_gather_tokens(k, v, ctypes.byref(ok), tb, mb, pos, b, None)
+    assert ga(b=0) == 0
+    assert ga(k=0) == -1 and ga(v=0) == -1 and ga(tb=0) == -1 and ga(pos=0) == -1
+    assert ga(b=-1) == -2 and ga(mb=0) == -2 and ga(v=0x30004) == -4
     co = lambda bm=0x60000, nb=100, ids=0x70000, cap=10, cnt=0x80000: \
         lib.kv_collect_dirty(bm, nb, ids, cap, cnt, 1, None)
     assert co(bm=0) == -1 and co(cnt=0) == -1 and co(ids=0) == -1

@@ -538,3 +538,47 @@ def test_fp8_pack_restore_move_bytes(oracle):
     tgt = np.zeros_like(case.pool)
     oracle.restore_blocks(tgt, rep, ids)
     assert np.array_equal(tgt[ids], case.pool[ids])
+
+
+# ---- token-granular replication: gather the new rows, append them on the target ------------------
+def test_gather_tokens_matches_numpy_indexing_and_inverts_append(oracle):
+    case = small_case(seed=81, lens=(6, 31, 70))
+    g = case.geom
+    pos = (case.context_lens - 1).astype(np.int32)                   # the newest token of every sequence
+    pos[1] = -1
+    k, v = oracle.gather_tokens(case.pool, case.block_table, pos)
+    for b in (0, 2):
+        pid, r = case.block_table[b, pos[b] // g.block_size], pos[b] % g.block_size
+        assert np.array_equal(k[b], case.pool[pid, 0, :, r, :]) and np.array_equal(v[b], case.pool[pid, 1, :, r, :])
+    assert not k[1].any() and not v[1].any()
+    # append(gather(x)) on a pool whose rows were wiped restores x; and the other way round
+    wiped = case.pool.copy()
+    for b in (0, 2):
+        pid, r = case.block_table[b, pos[b] // g.block_size], pos[b] % g.block_size
+        wiped[pid, :, :, r, :] = 0
+    bitmap = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    oracle.append_tokens(wiped, k, v, case.block_table, pos, bitmap)
+    assert np.array_equal(wiped, case.pool)
+    k_new, v_new = new_tokens(case, 8)
+    pool2 = case.pool.copy()
+    oracle.append_tokens(pool2, k_new, v_new, case.block_table, pos, bitmap)
+    k2, v2 = oracle.gather_tokens(pool2, case.block_table, pos)
+    assert np.array_equal(k2[[0, 2]], k_new[[0, 2]]) and np.array_equal(v2[[0, 2]], v_new[[0, 2]])
+
+
+def test_token_granular_replication_keeps_decode_output(oracle):
+    """Ship only the new rows: the target, which already holds the older state, decodes the same."""
+    case = small_case(seed=83, lens=(20, 50, 100))
+    g = case.geom
+    target = case.pool.copy()                                        # replica of the state before the step
+    k_new, v_new = new_tokens(case, 9)
+    src = case.pool.copy()
+    bm = np.zeros(oracle.bitmap_words(case.num_blocks), np.uint32)
+    oracle.append_tokens(src, k_new, v_new, case.block_table, case.context_lens, bm)
+    k, v = oracle.gather_tokens(src, case.block_table, case.context_lens)        # what travels: B*Hkv*D*2 elements
+    assert k.nbytes + v.nbytes == case.batch * g.kv_bytes_per_token
+    oracle.append_tokens(target, k, v, case.block_table, case.context_lens, bm)
+    assert np.array_equal(target, src)
+    a = oracle.decode_attn(case.q, src, case.block_table, case.context_lens + 1, g.scale)
+    b = oracle.decode_attn(case.q, target, case.block_table, case.context_lens + 1, g.scale)
+    assert np.array_equal(a, b)
