@@ -28,9 +28,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
 # HBM traffic per decode launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
 # WRITE_SIZE), scaled by the same counters on a plain copy of known size; see profiles/.  Valid
-# only for the kernel source the counters were taken with.
-DECODE_TRAFFIC = {"kernel_sha256": "59ba9a9aef279654f970027b227ceda09abdf19d5d678f773784413e7a008b3e",
-                  "fetch_bytes": 1329249661, "write_bytes": 4525431}
+# only for the kernel sources (kv_decode.hip + kv_decode_common.h) the counters were taken with.
+DECODE_TRAFFIC = {"kernel_sha256": "5f5326fb0d0c0284415bd4c147c147866523efe278b26ee5c63f3a3f5be681d2",
+                  "fetch_bytes": 1329065086, "write_bytes": 4525947}
 
 PAPER_CONTEXT = {
     "note": "end-to-end serving figures from the paper, other hardware, context only",
@@ -414,7 +414,8 @@ def main():
     g = case.geom
     d = main_res["decode"]
     achieved = main_res["decode_GBps"]
-    src = open(os.path.join(ROOT, "paper_2601_22438_amd", "csrc", "kv_decode.hip"), "rb").read()
+    src = b"".join(open(os.path.join(ROOT, "paper_2601_22438_amd", "csrc", f), "rb").read()
+                   for f in ("kv_decode.hip", "kv_decode_common.h"))
     traffic = None
     if DECODE_TRAFFIC["kernel_sha256"] == hashlib.sha256(src).hexdigest():
         traffic = DECODE_TRAFFIC["fetch_bytes"] + DECODE_TRAFFIC["write_bytes"]
