@@ -12,5 +12,6 @@ from .kv_oracle import (  # noqa: F401
     decode_attn,
     gather_tokens,
     pack_blocks,
+    prefill_attn,
     restore_blocks,
 )

@@ -307,3 +307,66 @@ int kvo_gather_tokens(const uint16_t* pool, int64_t num_blocks, int num_kv_heads
     }
     return 0;
 }
+
+/*
+ * Prefill / recomputation over the paged cache (the fallback of Sec. 3.2 item 3: a node that
+ * dropped replicas under memory pressure recomputes them).  Sequence b has context_lens[b]
+ * tokens in the pool, the last q_len_b = q_starts[b + 1] - q_starts[b] of which are the query
+ * tokens of this call (their K/V rows are already in the pool).  Query token j of sequence b
+ * sits at position pos = context_lens[b] - q_len_b + j and attends causally: to the keys at
+ * positions 0 .. pos and to nothing later.  That is the decode definition above with the
+ * context cut off after pos, which is how it is written here.  A query whose position would be
+ * negative (q_len_b > context_lens[b]) has no key and gives a row of zeros.
+ *
+ * q: bf16 [total_q][num_q_heads][head_dim], sequences packed in batch order (total_q =
+ * q_starts[batch]).  rows: optional list of n_rows (t, h) pairs, t a packed query-token index;
+ * when NULL every (t, h) is computed and out is [total_q][num_q_heads][head_dim], otherwise
+ * out is [n_rows][head_dim].  Returns the number of threads used or a negative error.
+ */
+int kvo_prefill_attn(double* out, const uint16_t* q, const void* pool, int kv_fp8, float k_scale, float v_scale,
+                     int64_t num_blocks, int num_kv_heads, int block_size, int head_dim,
+                     const int32_t* block_table, int max_blocks_per_seq,
+                     const int32_t* context_lens, const int32_t* q_starts, int batch, int num_q_heads,
+                     float scale, const int32_t* rows, int64_t n_rows, int num_threads)
+{
+    int rc = check_decode_args(num_blocks, num_kv_heads, block_size, head_dim, block_table,
+                               max_blocks_per_seq, context_lens, batch, num_q_heads);
+    if (rc) return rc;
+    if (q_starts[0] != 0) return -2;
+    for (int b = 0; b < batch; ++b) if (q_starts[b + 1] < q_starts[b]) return -2;
+    pool_view pv = { pool, num_blocks, num_kv_heads, block_size, head_dim, kv_fp8 != 0,
+                     kv_fp8 ? (double)k_scale : 1.0, kv_fp8 ? (double)v_scale : 1.0 };
+    const int G = num_q_heads / num_kv_heads;
+    const int64_t total_q = q_starts[batch];
+    const int64_t total = rows ? n_rows : total_q * num_q_heads;
+    int maxL = 1;
+    for (int b = 0; b < batch; ++b) if (context_lens[b] > maxL) maxL = context_lens[b];
+    int used = 1;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+#pragma omp parallel
+#endif
+    {
+        double* s = (double*)malloc(sizeof(double) * (size_t)maxL);
+        double* w = (double*)malloc(sizeof(double) * (size_t)maxL);
+#ifdef _OPENMP
+#pragma omp single
+        used = omp_get_num_threads();
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t i = 0; i < total; ++i) {
+            int64_t t = rows ? rows[2 * i] : i / num_q_heads;
+            int h = rows ? rows[2 * i + 1] : (int)(i % num_q_heads);
+            int b = 0;
+            while (b + 1 < batch && q_starts[b + 1] <= t) ++b;      /* the sequence that owns packed token t */
+            int q_len = q_starts[b + 1] - q_starts[b];
+            int pos = context_lens[b] - q_len + (int)(t - q_starts[b]);
+            decode_row(out + i * head_dim, q + (t * num_q_heads + h) * head_dim, &pv,
+                       block_table + (int64_t)b * max_blocks_per_seq, pos < 0 ? 0 : pos + 1, h / G,
+                       (double)scale, s, w);
+        }
+        free(s);
+        free(w);
+    }
+    return used;
+}

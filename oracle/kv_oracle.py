@@ -6,6 +6,7 @@ numpy ``uint16`` arrays holding the bit patterns.
 
 Operations (paper Sec. 3.2 item 3, Background KV Cache Replication):
 ``decode_attn``  attention of one query token per sequence over a block-paged cache;
+``prefill_attn`` causal attention of many query tokens per sequence over the same cache (recomputation);
 ``pack_blocks``  replica[i] <- pool[ids[i]] (block-by-block replication, gather side);
 ``restore_blocks`` pool[ids[i]] <- replica[i] (continuing from the replicated state).
 """
@@ -57,6 +58,12 @@ def _load():
             f64p, u16p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_float,
             ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             i32p, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_float,
+            i32p, ctypes.c_int64, ctypes.c_int]
+        lib.kvo_prefill_attn.restype = ctypes.c_int
+        lib.kvo_prefill_attn.argtypes = [
+            f64p, u16p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_float,
+            ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            i32p, ctypes.c_int, i32p, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_float,
             i32p, ctypes.c_int64, ctypes.c_int]
         u32p = ctypes.POINTER(ctypes.c_uint32)
         lib.kvo_append_tokens.restype = ctypes.c_int
@@ -130,6 +137,48 @@ def decode_attn(q, pool, block_table, context_lens, scale, rows=None, num_thread
         int(fp8), float(np.float32(k_scale)), float(np.float32(v_scale)), NB, Hkv, bs, D, _ptr(block_table, ctypes.c_int32), block_table.shape[1],
         _ptr(context_lens, ctypes.c_int32), B, Hq, float(np.float32(scale)),
         rows_p, n_rows, int(num_threads)))
+    return (out, used) if return_threads else out
+
+
+def prefill_attn(q, pool, block_table, context_lens, q_starts, scale, rows=None, num_threads=0,
+                 return_threads=False, k_scale=1.0, v_scale=1.0):
+    """fp64 causal attention of many query tokens per sequence over the block-paged cache.
+
+    q            uint16 [T][Hq][D]   bf16 bit patterns; the query tokens of all sequences, packed in batch order
+    pool, block_table, context_lens, scale, k_scale, v_scale   as for decode_attn; context_lens[b] counts
+                 the query tokens too (their K/V rows are in the pool already)
+    q_starts     int32 [B + 1]       q_starts[b] = first packed row of sequence b; q_starts[B] = T
+    rows         optional int32 [n][2] of (t, h), t a packed token index: compute only these -> [n][D]
+    Query token j of sequence b is at position context_lens[b] - q_len_b + j and sees keys 0 .. position.
+    Returns float64 [T][Hq][D] (or [n][D]).
+    """
+    q = _c(q, np.uint16)
+    pool = np.ascontiguousarray(pool)
+    if pool.dtype not in (np.uint16, np.uint8):
+        raise TypeError("pool must be uint16 (bf16) or uint8 (FP8 E4M3)")
+    fp8 = pool.dtype == np.uint8
+    block_table = _c(block_table, np.int32)
+    context_lens = _c(context_lens, np.int32)
+    q_starts = _c(q_starts, np.int32)
+    T, Hq, D = q.shape
+    NB, two, Hkv, bs, D2 = pool.shape
+    B = len(context_lens)
+    if two != 2 or D2 != D or block_table.shape[0] != B or q_starts.shape != (B + 1,) or int(q_starts[B]) != T:
+        raise OracleError("inconsistent shapes")
+    if rows is None:
+        out = np.empty((T, Hq, D), dtype=np.float64)
+        rows_p, n_rows = None, 0
+    else:
+        rows = _c(rows, np.int32).reshape(-1, 2)
+        if len(rows) and (rows.min() < 0 or rows[:, 0].max() >= T or rows[:, 1].max() >= Hq):
+            raise OracleError("row index out of range")
+        out = np.empty((len(rows), D), dtype=np.float64)
+        rows_p, n_rows = _ptr(rows, ctypes.c_int32), len(rows)
+    used = _check(_load().kvo_prefill_attn(
+        _ptr(out, ctypes.c_double), _ptr(q, ctypes.c_uint16), pool.ctypes.data_as(ctypes.c_void_p),
+        int(fp8), float(np.float32(k_scale)), float(np.float32(v_scale)), NB, Hkv, bs, D,
+        _ptr(block_table, ctypes.c_int32), block_table.shape[1], _ptr(context_lens, ctypes.c_int32),
+        _ptr(q_starts, ctypes.c_int32), B, Hq, float(np.float32(scale)), rows_p, n_rows, int(num_threads)))
     return (out, used) if return_threads else out
 
 

@@ -353,3 +353,84 @@ def materialise_recovered_pool(case: RecoveryCase, first_block=0, n_blocks=None)
     pool = np.zeros((case.num_blocks, 2, g.num_kv_heads, g.block_size, g.head_dim), dtype=np.uint16)
     pool[case.restore_ids[first_block:first_block + n_blocks]] = case.replica_chunk(first_block, n_blocks)
     return pool
+
+
+# ----------------------------------------------------------------------------------------------
+# Prefill / recomputation cases: many query tokens per sequence over the same kind of pool.
+# ----------------------------------------------------------------------------------------------
+
+@dataclass
+class PrefillCase:
+    """A decode case (pool, block table, context lengths) whose last q_lens[b] tokens are queries."""
+    name: str
+    kv: DecodeCase                      # kv.q is unused here
+    q_lens: np.ndarray                  # int32 [B], q_lens[b] <= context_lens[b]
+    q_starts: np.ndarray                # int32 [B + 1], exclusive prefix sum of q_lens
+    q: np.ndarray                       # uint16 [T][Hq][D], T = q_starts[B]
+
+    @property
+    def geom(self) -> Geometry:
+        return self.kv.geom
+
+    @property
+    def batch(self) -> int:
+        return self.kv.batch
+
+    @property
+    def total_q(self) -> int:
+        return int(self.q_starts[-1])
+
+    @property
+    def max_q_len(self) -> int:
+        return int(self.q_lens.max()) if len(self.q_lens) else 0
+
+    @property
+    def pairs(self) -> int:
+        """(query, key) pairs inside the causal mask, per query head."""
+        L = self.kv.context_lens.astype(np.int64)
+        n = self.q_lens.astype(np.int64)
+        # query j of a sequence sees L - n + j + 1 keys
+        return int((n * (L - n) + n * (n + 1) // 2).sum())
+
+    @property
+    def flops(self) -> int:
+        """Multiply-adds of Q K^T and P V counted as 2 flops each."""
+        g = self.geom
+        return 4 * g.head_dim * g.num_q_heads * self.pairs
+
+
+def make_prefill_case(name, seed, geom: Geometry, context_lens, q_lens, **kw) -> PrefillCase:
+    kv = make_decode_case(name, seed, geom, context_lens, **kw)
+    q_lens = np.asarray(q_lens, dtype=np.int32)
+    if q_lens.shape != kv.context_lens.shape or (q_lens < 0).any() or (q_lens > kv.context_lens).any():
+        raise ValueError("q_lens must lie in [0, context_lens]")
+    q_starts = np.zeros(len(q_lens) + 1, dtype=np.int32)
+    np.cumsum(q_lens, out=q_starts[1:])
+    ss_q = np.random.SeedSequence([seed, 0x7072656669])
+    q = normal_bf16(ss_q, (int(q_starts[-1]), geom.num_q_heads, geom.head_dim))
+    return PrefillCase(name, kv, q_lens, q_starts, q)
+
+
+def prefill_tiny(seed=5) -> PrefillCase:
+    """Small geometry; sequences recomputed in full, in part, by a single token, and not at all."""
+    g = Geometry(8, 2, 64, 16)
+    lens = np.array([97, 256, 1, 130, 64, 200], np.int32)
+    q_lens = np.array([97, 100, 1, 1, 0, 65], np.int32)
+    return make_prefill_case("prefill_tiny", seed, g, lens, q_lens, num_blocks=128, max_blocks_per_seq=16,
+                             dirty="any", n_dirty=8)
+
+
+def recompute(seed=6, shrink=1, batch=8) -> PrefillCase:
+    """Whole sequences recomputed after their replicas were dropped: q_len = context length."""
+    g = Geometry(32, 8, 128, 16)
+    lens = _uniform_lens(seed, batch, 2048 // shrink, 8192 // shrink)
+    return make_prefill_case("recompute", seed, g, lens, lens, max_blocks_per_seq=512 // shrink, dirty="last")
+
+
+def chunked_recompute(seed=7, shrink=1, batch=8, chunk=2048) -> PrefillCase:
+    """The newest ``chunk`` tokens of long sequences recomputed over a restored prefix."""
+    g = Geometry(32, 8, 128, 16)
+    lens = _uniform_lens(seed, batch, 16384 // shrink, 65536 // shrink)
+    q_lens = np.minimum(lens, max(1, chunk // shrink)).astype(np.int32)
+    return make_prefill_case("chunked_recompute", seed, g, lens, q_lens, max_blocks_per_seq=4096 // shrink,
+                             dirty="last")

@@ -1,0 +1,188 @@
+"""Pins of the prefill (recomputation) oracle against things other than itself (no GPU).
+
+The paper states only that dropped replicas are recomputed (Sec. 3.2 item 3); what is recomputed is
+ordinary causal attention over the tokens of a sequence.  The oracle is therefore held by a library
+routine (torch SDPA in fp64, with its own causal mask), an independently written dense numpy
+attention, closed forms and invariants, each chosen so that one plausible mistake (mask off by one,
+queries aligned to the start instead of the end of the context, wrong packed-row offset, wrong head
+mapping) fails it.
+"""
+import numpy as np
+import pytest
+
+from paper_2601_22438_amd import workloads as W
+from test_oracle_pins import gather_contiguous
+
+
+def small_prefill(seed=21, Hq=8, Hkv=2, D=64, bs=16, lens=(40, 70, 5, 33), q_lens=(40, 17, 1, 0), NB=48):
+    g = W.Geometry(Hq, Hkv, D, bs)
+    return W.make_prefill_case("small_prefill", seed, g, np.array(lens, np.int32), np.array(q_lens, np.int32),
+                               num_blocks=NB, max_blocks_per_seq=8, dirty="any", n_dirty=4)
+
+
+def run(oracle, case, **kw):
+    kv = case.kv
+    return oracle.prefill_attn(case.q, kv.pool, kv.block_table, kv.context_lens, case.q_starts,
+                               case.geom.scale, **kw)
+
+
+def dense_causal(case):
+    """Independent numpy version on contiguous K/V: explicit position mask, softmax over the last axis."""
+    g = case.geom
+    scale = float(np.float32(g.scale))
+    q = W.bf16_bits_to_f32(case.q).astype(np.float64)
+    ks, vs = gather_contiguous(case.kv)
+    out = np.zeros(q.shape)
+    for b in range(case.batch):
+        n, L = int(case.q_lens[b]), int(case.kv.context_lens[b])
+        if n == 0:
+            continue
+        qb = q[case.q_starts[b]:case.q_starts[b + 1]]                # [n][Hq][D]
+        k = np.repeat(ks[b], g.group, axis=1)                        # [L][Hq][D]
+        v = np.repeat(vs[b], g.group, axis=1)
+        s = np.einsum("nhd,lhd->hnl", qb, k) * scale
+        q_pos = L - n + np.arange(n)
+        visible = np.arange(L)[None, :] <= q_pos[:, None]            # [n][L]
+        s = np.where(visible[None], s, -np.inf)
+        p = np.exp(s - s.max(axis=2, keepdims=True))
+        p /= p.sum(axis=2, keepdims=True)
+        out[case.q_starts[b]:case.q_starts[b + 1]] = np.einsum("hnl,lhd->nhd", p, v)
+    return out
+
+
+@pytest.mark.parametrize("geom", [(8, 2, 64, 16), (4, 4, 128, 16), (16, 2, 128, 32), (6, 3, 64, 16)])
+def test_matches_dense_numpy_attention(oracle, geom):
+    Hq, Hkv, D, bs = geom
+    case = small_prefill(seed=22, Hq=Hq, Hkv=Hkv, D=D, bs=bs)
+    np.testing.assert_allclose(run(oracle, case), dense_causal(case), rtol=0, atol=1e-12)
+
+
+def test_prefill_tiny_matches_dense_numpy_attention(oracle):
+    case = W.prefill_tiny()
+    np.testing.assert_allclose(run(oracle, case), dense_causal(case), rtol=0, atol=1e-12)
+
+
+def test_full_recompute_matches_torch_causal_sdpa(oracle):
+    """q_len = context length: the library's own is_causal mask (top-left aligned = bottom-right here)."""
+    import torch
+    case = small_prefill(seed=23, lens=(40, 19, 64), q_lens=(40, 19, 64))
+    g = case.geom
+    got = run(oracle, case)
+    ks, vs = gather_contiguous(case.kv)
+    q = torch.from_numpy(W.bf16_bits_to_f32(case.q).astype(np.float64))
+    for b in range(case.batch):
+        qb = q[case.q_starts[b]:case.q_starts[b + 1]].permute(1, 0, 2)                    # [Hq][n][D]
+        k = torch.from_numpy(ks[b]).permute(1, 0, 2).repeat_interleave(g.group, dim=0)    # [Hq][L][D]
+        v = torch.from_numpy(vs[b]).permute(1, 0, 2).repeat_interleave(g.group, dim=0)
+        ref = torch.nn.functional.scaled_dot_product_attention(qb, k, v, is_causal=True,
+                                                               scale=float(np.float32(g.scale)))
+        np.testing.assert_allclose(got[case.q_starts[b]:case.q_starts[b + 1]], ref.permute(1, 0, 2).numpy(),
+                                   rtol=0, atol=1e-12)
+
+
+def test_chunk_over_a_prefix_matches_the_tail_of_a_full_recompute(oracle):
+    """The last n query rows of a full causal pass (library routine) are what a chunk of n queries gives."""
+    import torch
+    case = small_prefill(seed=24, lens=(50, 70), q_lens=(13, 33))
+    g = case.geom
+    got = run(oracle, case)
+    ks, vs = gather_contiguous(case.kv)
+    q = W.bf16_bits_to_f32(case.q).astype(np.float64)
+    for b in range(case.batch):
+        n, L = int(case.q_lens[b]), int(case.kv.context_lens[b])
+        full_q = np.zeros((L, g.num_q_heads, g.head_dim))
+        full_q[L - n:] = q[case.q_starts[b]:case.q_starts[b + 1]]
+        k = torch.from_numpy(ks[b]).permute(1, 0, 2).repeat_interleave(g.group, dim=0)
+        v = torch.from_numpy(vs[b]).permute(1, 0, 2).repeat_interleave(g.group, dim=0)
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(full_q).permute(1, 0, 2), k, v, is_causal=True, scale=float(np.float32(g.scale)))
+        np.testing.assert_allclose(got[case.q_starts[b]:case.q_starts[b + 1]],
+                                   ref.permute(1, 0, 2).numpy()[L - n:], rtol=0, atol=1e-12)
+
+
+def test_single_query_is_decode(oracle):
+    """One query token per sequence, at the end of its context: the decode operation, which has its own pins."""
+    case = small_prefill(seed=25, lens=(40, 70, 5, 33), q_lens=(1, 1, 1, 1))
+    kv = case.kv
+    got = run(oracle, case)
+    dec = oracle.decode_attn(case.q.reshape(case.batch, *case.q.shape[1:]), kv.pool, kv.block_table,
+                             kv.context_lens, case.geom.scale)
+    assert np.array_equal(got, dec)
+
+
+def test_first_token_returns_its_own_value_row(oracle):
+    """Position 0 sees one key: the output is V[0] exactly, whatever q and K are."""
+    case = small_prefill(seed=26, lens=(20, 33), q_lens=(20, 33))
+    g = case.geom
+    got = run(oracle, case)
+    v = W.bf16_bits_to_f32(case.kv.pool).astype(np.float64)
+    for b in range(case.batch):
+        p = case.kv.block_table[b, 0]
+        for h in range(g.num_q_heads):
+            assert np.array_equal(got[case.q_starts[b], h], v[p, 1, h // g.group, 0])
+
+
+def test_zero_queries_give_running_means_of_v(oracle):
+    """All scores equal: query at position p returns the mean of V[0..p]."""
+    case = small_prefill(seed=27, lens=(37, 50), q_lens=(37, 21))
+    case.q[:] = 0
+    got = run(oracle, case)
+    _, vs = gather_contiguous(case.kv)
+    for b in range(case.batch):
+        n, L = int(case.q_lens[b]), int(case.kv.context_lens[b])
+        run_mean = np.cumsum(vs[b], axis=0) / np.arange(1, L + 1)[:, None, None]          # [L][Hkv][D]
+        want = np.repeat(run_mean[L - n:], case.geom.group, axis=1)
+        np.testing.assert_allclose(got[case.q_starts[b]:case.q_starts[b + 1]], want, rtol=1e-13, atol=1e-14)
+
+
+def test_later_tokens_do_not_influence_earlier_queries(oracle):
+    """Changing K/V at position p changes exactly the queries at positions >= p."""
+    case = small_prefill(seed=28, lens=(48,), q_lens=(48,), NB=8)
+    g = case.geom
+    before = run(oracle, case)
+    p = 29
+    blk, row = case.kv.block_table[0, p // g.block_size], p % g.block_size
+    case.kv.pool[blk, :, :, row, :] ^= 0x0040                        # flip a mantissa bit of K and V rows
+    after = run(oracle, case)
+    assert np.array_equal(before[:p], after[:p])
+    assert (np.abs(before[p:] - after[p:]).max(axis=(1, 2)) > 0).all()
+
+
+def test_queries_are_aligned_to_the_end_of_the_context(oracle):
+    """Two sequences share one pool prefix; the longer chunk's last rows equal the shorter chunk's rows."""
+    a = small_prefill(seed=29, lens=(60,), q_lens=(25,), NB=8)
+    b = small_prefill(seed=29, lens=(60,), q_lens=(9,), NB=8)
+    b.q[:] = a.q[25 - 9:]
+    ga, gb = run(oracle, a), run(oracle, b)
+    assert np.array_equal(ga[25 - 9:], gb)
+
+
+def test_packed_rows_follow_q_starts(oracle):
+    """Batched call = the sequences run one at a time and concatenated."""
+    case = small_prefill(seed=30)
+    kv = case.kv
+    got = run(oracle, case)
+    for b in range(case.batch):
+        lo, hi = int(case.q_starts[b]), int(case.q_starts[b + 1])
+        one = oracle.prefill_attn(case.q[lo:hi], kv.pool, kv.block_table[b:b + 1], kv.context_lens[b:b + 1],
+                                  np.array([0, hi - lo], np.int32), case.geom.scale)
+        assert np.array_equal(got[lo:hi], one)
+
+
+def test_rows_subset_matches_full(oracle):
+    case = small_prefill(seed=31)
+    full = run(oracle, case)
+    rows = np.array([[0, 0], [39, 7], [40, 3], [56, 1], [57, 6]], np.int32)
+    sub = run(oracle, case, rows=rows)
+    for i, (t, h) in enumerate(rows):
+        assert np.array_equal(sub[i], full[t, h])
+
+
+def test_more_queries_than_context_gives_zero_rows_for_the_excess(oracle):
+    case = small_prefill(seed=32, lens=(10,), q_lens=(10,), NB=4)
+    kv = case.kv
+    q = np.concatenate([case.q[:3], case.q])                         # 13 queries over 10 cached tokens
+    got = oracle.prefill_attn(q, kv.pool, kv.block_table, kv.context_lens, np.array([0, 13], np.int32),
+                              case.geom.scale)
+    assert np.array_equal(got[:3], np.zeros_like(got[:3]))
+    assert np.array_equal(got[3:], run(oracle, case))
