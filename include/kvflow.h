@@ -128,6 +128,38 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Recomputation of attention state over the paged cache (Sec. 3.2 item 3: a node that dropped
+ * replicas under memory pressure recomputes them): causal attention of many query tokens per
+ * sequence.  Sequence b has L = context_lens[b] tokens in the pool, the newest
+ * n = q_starts[b+1] - q_starts[b] of which are this call's query tokens (their K/V rows are in
+ * the pool already, e.g. written by kv_append_tokens or restored from a replica).  Query token i
+ * of sequence b (packed row t = q_starts[b] + i) sits at position pos = L - n + i and, with
+ * kvh = h / (num_q_heads / num_kv_heads):
+ *     s[u]       = scale * sum_d q[t,h,d] * K[table[b][u / bs], kvh, u % bs, d]     0 <= u <= pos
+ *     out[t,h,:] = sum_u softmax(s)[u] * V[table[b][u / bs], kvh, u % bs, :]
+ * bf16 inputs, fp32 accumulation.  n == 1 is kv_decode_attn's operation.  A query with pos < 0
+ * (n > L) sees no key and gives a row of zeros.
+ *
+ *   out            [total_q][num_q_heads][head_dim], out_dtype KV_DTYPE_BF16 or KV_DTYPE_F32, written;
+ *                  total_q = q_starts[batch]
+ *   q              [total_q][num_q_heads][head_dim] bf16, read; sequences packed in batch order
+ *   pool           host struct; bf16 pool, read
+ *   block_table    int32 [batch][max_blocks_per_seq], read; only the first ceil(L/bs) entries of a row
+ *   context_lens   int32 [batch], read; counts the query tokens too
+ *   q_starts       int32 [batch + 1], read; non-decreasing, q_starts[0] == 0
+ *   max_q_len      host-side upper bound of the n above; sizes the grid
+ * Preconditions on device contents: 0 <= context_lens[b] <= max_blocks_per_seq * bs; table entries as
+ * for kv_decode_attn; 0 <= n <= max_q_len.
+ * Needs no workspace.  The result depends only on logical token positions.
+ * Errors: NULL, SHAPE, UNSUPPORTED (head_dim, block_size, FP8 pool, batch or num_q_heads > 65535,
+ * max_q_len > 65535 * 64), ALIGN, LAUNCH.  batch == 0 or max_q_len == 0 returns KV_OK without a launch.
+ */
+int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
+                    const int32_t* block_table, int32_t max_blocks_per_seq,
+                    const int32_t* context_lens, const int32_t* q_starts, int32_t batch,
+                    int32_t num_q_heads, int32_t max_q_len, float scale, void* stream);
+
+/*
  * Gather side of block-by-block replication (Sec. 3.2 item 3; meant to run on a
  * stream of its own beside decode, Sec. 4.4):
  *     replica[i] <- pool[block_ids[i]]   for i in [0, n), whole blocks, list order.

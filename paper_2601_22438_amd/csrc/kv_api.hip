@@ -167,6 +167,44 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
     return KV_OK;
 }
 
+int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
+                    const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* context_lens,
+                    const int32_t* q_starts, int32_t batch, int32_t num_q_heads, int32_t max_q_len,
+                    float scale, void* stream)
+{
+    int rc = check_pool(pool);
+    if (rc != KV_OK) return rc;
+    if (batch < 0 || num_q_heads <= 0 || max_blocks_per_seq <= 0 || max_q_len < 0) return KV_ERR_SHAPE;
+    if (num_q_heads % pool->num_kv_heads) return KV_ERR_SHAPE;
+    if (pool->dtype != KV_DTYPE_BF16) return KV_ERR_UNSUPPORTED;
+    if (out_dtype != KV_DTYPE_BF16 && out_dtype != KV_DTYPE_F32) return KV_ERR_UNSUPPORTED;
+    if (batch > 65535 || num_q_heads > 65535) return KV_ERR_UNSUPPORTED;
+    if ((int64_t)max_q_len > (int64_t)65535 * 16 * kPrefillQueryBlocks) return KV_ERR_UNSUPPORTED;
+    if (batch == 0 || max_q_len == 0) return KV_OK;
+    if (!out || !q || !block_table || !context_lens || !q_starts) return KV_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q)) return KV_ERR_ALIGN;
+    const int32_t group = num_q_heads / pool->num_kv_heads;
+    PrefillParams p;
+    p.out = out;
+    p.q = (const uint16_t*)q;
+    p.pool = (const uint16_t*)pool->base;
+    p.block_table = block_table;
+    p.context_lens = context_lens;
+    p.q_starts = q_starts;
+    p.max_blocks_per_seq = max_blocks_per_seq;
+    p.batch = batch;
+    p.num_q_heads = num_q_heads;
+    p.num_kv_heads = pool->num_kv_heads;
+    p.group = group;
+    p.heads_per_wg = group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+    p.block_size = pool->block_size;
+    p.block_shift = pool->block_size == 16 ? 4 : 5;
+    p.out_f32 = out_dtype == KV_DTYPE_F32;
+    p.scale_log2e = (float)((double)scale * 1.4426950408889634074);
+    hipError_t e = launch_prefill(p, pool->head_dim, max_q_len, (hipStream_t)stream);
+    return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
+}
+
 int kv_pack_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n, void* stream)
 {
     return copy_blocks(replica, pool, block_ids, n, nullptr, true, stream);

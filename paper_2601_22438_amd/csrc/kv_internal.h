@@ -44,6 +44,28 @@ hipError_t launch_decode(const DecodeParams& p, int head_dim, int workgroups, hi
 hipError_t launch_decode_fp8(const DecodeParams& p, int head_dim, int workgroups, hipStream_t stream);
 constexpr int kFp8TileTokens = 64;
 
+// Prefill (recomputation): a workgroup is 4 wavefronts, each owning 16 * kPrefillQueryBlocks query rows.
+constexpr int kPrefillWaves = 4;
+constexpr int kPrefillThreads = kPrefillWaves * 64;
+constexpr int kPrefillQueryBlocks = 2;
+
+struct PrefillParams {
+    void* out;                 // [total_q][Hq][D] bf16 or fp32
+    const uint16_t* q;         // [total_q][Hq][D] bf16
+    const uint16_t* pool;      // [NB][2][Hkv][bs][D] bf16
+    const int32_t* block_table;
+    const int32_t* context_lens;
+    const int32_t* q_starts;   // [batch + 1]
+    int32_t max_blocks_per_seq;
+    int32_t batch, num_q_heads, num_kv_heads, group;
+    int32_t heads_per_wg;      // 4, 2 or 1 query heads of one group per workgroup (divides group)
+    int32_t block_size, block_shift;
+    int32_t out_f32;
+    float scale_log2e;
+};
+
+hipError_t launch_prefill(const PrefillParams& p, int head_dim, int max_q_len, hipStream_t stream);
+
 // dst/src are the replica and the pool; to_replica selects the direction.  count (device, may be
 // NULL) limits the list to its first *count entries; n then is the launch bound.
 hipError_t launch_copy_blocks(void* replica, void* pool, size_t block_bytes, const int32_t* block_ids,

@@ -1,0 +1,318 @@
+// Causal attention of many query tokens per sequence over the block-paged KV cache: the
+// recomputation that a node falls back to when it dropped replicas (paper Sec. 3.2 item 3).
+// The query tokens are the newest q_len tokens of a sequence whose K/V rows are in the pool
+// already; query j sits at position context_len - q_len + j and sees keys 0 .. its position.
+//
+// This is a dense contraction (4 * head_dim flops per (query, key) pair), bound by the matrix
+// cores, not by HBM.  A workgroup of 4 wavefronts walks the keys of one (sequence, KV head) in
+// 32-token tiles that it stages in LDS once (double-buffered, next tile's global loads in
+// flight) and that all 4 wavefronts consume.  Each wavefront owns 16 * NQB query rows: query
+// tokens of one query head, so the 4 wavefronts are the 4 query heads of a group over the same
+// token range when the group allows it (same causal extent, K/V shared), else neighbouring token
+// ranges.  Per tile and wavefront, in the same transposed orientation as the decode kernel:
+//     S^T[key][query] = K[key][d] * Q^T[d][query]          (v_mfma_f32_16x16x32_bf16)
+//     O^T[d][query]  += V^T[d][key] * P^T[key][query]
+// so a lane's softmax statistics belong to one query (lane % 16), P leaves the first product in
+// the layout the second one wants, Q stays in registers for the whole kernel and every K/V
+// fragment read from LDS serves NQB MFMAs.
+//
+// Grid: x = query-head group (fastest, so that with 8 or more groups the workgroups that read
+// one KV head's tiles land on one XCD and share its L2), y = token range, heaviest (latest)
+// first, z = sequence.
+
+#include "kv_decode_common.h"
+
+namespace kvflow {
+
+template <int D>
+struct PrefillShape {
+    static constexpr int kSteps = D / 32;                 // MFMA k-steps over the head dimension
+    static constexpr int kDTiles = D / 16;                // 16-channel output tiles
+    static constexpr int kLanesPerRow = D / 8;            // lanes covering one K/V row with 16-byte loads
+    static constexpr int kRowsPerPass = kPrefillThreads / kLanesPerRow;
+    static constexpr int kPasses = kTileTokens / kRowsPerPass;
+    static constexpr int kKPitch = D * 2 + 16;            // LDS row pitches in bytes: 16 rows read by 16 lanes
+    static constexpr int kVPitch = D * 2 + 32;            // (K) / transposed 4x16 reads (V) hit distinct banks
+    static constexpr int kKBytes = kTileTokens * kKPitch;
+    static constexpr int kVBytes = kTileTokens * kVPitch;
+    static constexpr int kStage = kKBytes + kVBytes;
+};
+
+// Register budget of 2 wavefronts per SIMD (8 per compute unit, two workgroups): while one wavefront
+// of a SIMD is in its softmax (vector ALU) the other can keep the matrix core busy.
+template <int D, int NQB>
+__global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(
+    const PrefillParams p, const uint16_t* __restrict__ q_ptr, const uint16_t* __restrict__ pool_ptr,
+    const int32_t* __restrict__ table_ptr, const int32_t* __restrict__ lens_ptr,
+    const int32_t* __restrict__ qs_ptr, void* __restrict__ out_ptr)
+{
+    using S = PrefillShape<D>;
+    constexpr int QW = 16 * NQB;                          // query rows per wavefront
+    static_assert(kTileTokens == 32, "tile indices below are positions >> 5");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * S::kStage];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int b = blockIdx.z;
+    const int L = lens_ptr[b];
+    const int qs = qs_ptr[b];
+    const int n = qs_ptr[b + 1] - qs;
+    const int hpw = p.heads_per_wg, tbw = kPrefillWaves / hpw;
+    const int ntb = (n + QW - 1) / QW;                    // token ranges of this sequence
+    const int tbg = (ntb + tbw - 1) / tbw - 1 - (int)blockIdx.y;
+    if (tbg < 0) return;
+
+    const int head = blockIdx.x * hpw + wave % hpw;
+    const int kvh = (blockIdx.x * hpw) / p.group;
+    const int tb = tbg * tbw + wave / hpw;
+    const bool active = tb < ntb;                         // wave-uniform
+    const int j0 = tb * QW;
+    const int p0 = L - n;                                 // position of query 0 (negative: more queries than context)
+    const bool f32out = p.out_f32 != 0;
+
+    // query rows of this lane: query block qb, column j
+    int qidx[NQB], qpos[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        qidx[qb] = j0 + 16 * qb + j;
+        qpos[qb] = p0 + min(qidx[qb], n - 1);
+    }
+    auto store_rows = [&](const f32x4 (&o)[NQB][S::kDTiles], const float (&inv)[NQB]) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+            if (qidx[qb] >= n) continue;
+            const float f = qpos[qb] < 0 ? 0.f : inv[qb];           // a query before position 0 sees nothing
+            const int64_t row = ((int64_t)(qs + qidx[qb]) * p.num_q_heads + head) * D + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < S::kDTiles; ++dt) {
+                const f32x4 v = qpos[qb] < 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : o[qb][dt] * f;
+                if (f32out) {
+                    *(f32x4*)((float*)out_ptr + row + 16 * dt) = v;
+                } else {
+                    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+                    bf16x4 h;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) h[i] = (__bf16)v[i];
+                    *(bf16x4*)((__bf16*)out_ptr + row + 16 * dt) = h;
+                }
+            }
+        }
+    };
+
+    f32x4 oacc[NQB][S::kDTiles];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+        for (int dt = 0; dt < S::kDTiles; ++dt) oacc[qb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (L <= 0) {                                         // no cached token at all: rows of zeros
+        if (active) {
+            const float z[NQB] = {};
+            store_rows(oacc, z);
+        }
+        return;
+    }
+
+    // keys this workgroup walks: up to the position of its last query
+    const int jl = min((tbg * tbw + tbw) * QW, n) - 1;
+    const int nt = (max(p0 + jl, 0) >> 5) + 1;
+    // this wavefront: first query position (tiles that reach past it need the mask), last tile
+    const int pa = p0 + j0;
+    const int tl = active ? (max(p0 + min(j0 + QW, n) - 1, 0) >> 5) : -1;
+
+    // ---- global -> LDS staging of K/V tiles
+    const int bs = p.block_size;
+    const int64_t head_elems = (int64_t)bs * D;
+    const int64_t v_off = (int64_t)p.num_kv_heads * head_elems;
+    const int64_t blk_elems = 2 * v_off;
+    const int r = tid / S::kLanesPerRow, c = tid % S::kLanesPerRow;
+    const int32_t* trow = table_ptr + (int64_t)b * p.max_blocks_per_seq;
+    // rows past the last cached token are read from the last token's row (always mapped) and masked
+    auto load_ids = [&](int t, int (&ids)[S::kPasses]) {
+#pragma unroll
+        for (int ps = 0; ps < S::kPasses; ++ps) {
+            const int kp = min(kTileTokens * t + r + ps * S::kRowsPerPass, L - 1);
+            ids[ps] = trow[kp >> p.block_shift];
+        }
+    };
+    u32x4 kg[S::kPasses], vg[S::kPasses];
+    auto gload = [&](int t, const int (&ids)[S::kPasses]) {
+#pragma unroll
+        for (int ps = 0; ps < S::kPasses; ++ps) {
+            const int kp = min(kTileTokens * t + r + ps * S::kRowsPerPass, L - 1);
+            const uint16_t* src = pool_ptr + (int64_t)ids[ps] * blk_elems + (int64_t)kvh * head_elems +
+                                  (int64_t)(kp & (bs - 1)) * D + c * 8;
+            kg[ps] = *(const u32x4*)src;
+            vg[ps] = *(const u32x4*)(src + v_off);
+        }
+    };
+    auto lstore = [&](int t, unsigned char* buf) {
+#pragma unroll
+        for (int ps = 0; ps < S::kPasses; ++ps) {
+            const int rr = r + ps * S::kRowsPerPass;
+            // V rows past the end are zeroed: 0 * NaN must not reach the sum
+            const u32x4 v = kTileTokens * t + rr < L ? vg[ps] : u32x4{0u, 0u, 0u, 0u};
+            *(u32x4*)(buf + rr * S::kKPitch + c * 16) = kg[ps];
+            *(u32x4*)(buf + S::kKBytes + rr * S::kVPitch + c * 16) = v;
+        }
+    };
+
+    // ---- Q^T fragments: query column j of block qb, channels 32ks + 8g .. +7
+    bf16x8 qreg[NQB][S::kSteps];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        const uint16_t* qrow = q_ptr + ((int64_t)(qs + qidx[qb]) * p.num_q_heads + head) * D + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < S::kSteps; ++ks) {
+            u32x4 t = {0u, 0u, 0u, 0u};
+            if (active && qidx[qb] < n) t = *(const u32x4*)(qrow + 32 * ks);
+            qreg[qb][ks] = __builtin_bit_cast(bf16x8, t);
+        }
+    }
+    int qvis[NQB];                                        // last visible key position of the lane's queries
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) qvis[qb] = max(qpos[qb], 0);
+
+    float m_run[NQB], l_run[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+
+    const int k_off = j * S::kKPitch + 16 * g;            // K operand: row j, channels 8g ..
+    // transposed V read: lanes 4e+c of a 16-lane group point at row 4g+e, channels 4c..4c+3 of a d-tile
+    const int v_off_lds = S::kKBytes + (4 * g + (j >> 2)) * S::kVPitch + (j & 3) * 8;
+
+    auto compute = [&](int t, const unsigned char* buf, auto masked_tag) {
+        constexpr bool masked = decltype(masked_tag)::value;
+        // ---- S^T = K Q^T, two 16-key subtiles
+        f32x4 s[NQB][2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            bf16x8 kf[S::kSteps];
+#pragma unroll
+            for (int ks = 0; ks < S::kSteps; ++ks)
+                kf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(buf + k_off + u * 16 * S::kKPitch + ks * 64));
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) s[qb][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < S::kSteps; ++ks)
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb)
+                    s[qb][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qreg[qb][ks], s[qb][u], 0, 0, 0);
+        }
+        // ---- online softmax; lane (g, j): s[qb][u][i] is query column j of block qb, key 32t + 16u + 4g + i
+        float tt[NQB][8], mx[NQB];
+        bool raise = false;
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float x = s[qb][u][i] * p.scale_log2e;
+                    if (masked && kTileTokens * t + 16 * u + 4 * g + i > qvis[qb]) x = -INFINITY;
+                    tt[qb][4 * u + i] = x;
+                }
+            mx[qb] = fmaxf(fmaxf(fmaxf(tt[qb][0], tt[qb][1]), fmaxf(tt[qb][2], tt[qb][3])),
+                           fmaxf(fmaxf(tt[qb][4], tt[qb][5]), fmaxf(tt[qb][6], tt[qb][7])));
+            raise |= mx[qb] > m_run[qb] + kMaxSlack;
+        }
+        // wave-uniform: does any lane see a score above its query's running max by more than the slack?
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) {
+                float v = fmaxf(mx[qb], __shfl_xor(mx[qb], 16));
+                v = fmaxf(v, __shfl_xor(v, 32));
+                const float m_new = fmaxf(m_run[qb], v);
+                // tile 0 holds key 0, visible to every query, so m_new is finite from the first tile on
+                const float alpha = fast_exp2(m_run[qb] - m_new);
+                m_run[qb] = m_new;
+                l_run[qb] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < S::kDTiles; ++dt) oacc[qb][dt] *= alpha;
+            }
+        }
+        bf16x8 pb[NQB];
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+            float psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float pe = fast_exp2(tt[qb][e] - m_run[qb]);
+                psum += pe;
+                pb[qb][e] = (__bf16)pe;
+            }
+            l_run[qb] += psum;
+        }
+        // ---- O^T += V^T P^T over the tile's 32 keys, one 16-channel tile at a time
+#pragma unroll
+        for (int dt = 0; dt < S::kDTiles; ++dt) {
+            typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(buf + v_off_lds + dt * 32));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s16x4_ptr)(buf + v_off_lds + 16 * S::kVPitch + dt * 32));
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb)
+                oacc[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[qb], oacc[qb][dt], 0, 0, 0);
+        }
+    };
+
+    // ---- pipeline: tile t is consumed from buffer t & 1 while tile t + 1 goes registers -> LDS and
+    //      tile t + 2 global -> registers; block ids run one more tile ahead.  One barrier per tile.
+    //      Tiles past the end re-read the last rows (in bounds) and are never consumed.
+    int ids[S::kPasses];
+    load_ids(0, ids);
+    gload(0, ids);
+    load_ids(1, ids);
+    lstore(0, smem);
+    gload(1, ids);
+    load_ids(2, ids);
+    __syncthreads();
+    for (int t = 0; t < nt; ++t) {
+        unsigned char* cur = smem + (t & 1) * S::kStage;
+        unsigned char* nxt = smem + ((t + 1) & 1) * S::kStage;
+        lstore(t + 1, nxt);
+        gload(t + 2, ids);
+        load_ids(t + 3, ids);
+        if (t <= tl) {
+            if (kTileTokens * t + kTileTokens - 1 > pa) compute(t, cur, std::true_type{});
+            else compute(t, cur, std::false_type{});
+        }
+        __syncthreads();
+    }
+
+    if (active) {
+        float inv[NQB];
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+            float l = l_run[qb] + __shfl_xor(l_run[qb], 16);
+            l += __shfl_xor(l, 32);
+            inv[qb] = 1.f / l;
+        }
+        store_rows(oacc, inv);
+    }
+}
+
+template <int D>
+static hipError_t launch_prefill_d(const PrefillParams& p, int max_q_len, hipStream_t stream)
+{
+    constexpr int NQB = kPrefillQueryBlocks;
+    const int tbw = kPrefillWaves / p.heads_per_wg;
+    const int ranges = (max_q_len + 16 * NQB - 1) / (16 * NQB);
+    const dim3 grid((uint32_t)(p.num_q_heads / p.heads_per_wg), (uint32_t)((ranges + tbw - 1) / tbw),
+                    (uint32_t)p.batch);
+    if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((prefill_kernel<D, NQB>), grid, dim3(kPrefillThreads), 0, stream, p, p.q, p.pool,
+                       p.block_table, p.context_lens, p.q_starts, p.out);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill(const PrefillParams& p, int head_dim, int max_q_len, hipStream_t stream)
+{
+    if (head_dim == 128) return launch_prefill_d<128>(p, max_q_len, stream);
+    if (head_dim == 64) return launch_prefill_d<64>(p, max_q_len, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace kvflow

@@ -54,6 +54,8 @@ def load() -> ctypes.CDLL:
     lib.kv_decode_workspace_bytes.argtypes = [I32, I32, I32, I32, I32, I32]
     lib.kv_decode_attn.restype = ctypes.c_int
     lib.kv_decode_attn.argtypes = [P, I32, P, PD, P, I32, P, I32, I32, I32, F, I32, P, SZ, P]
+    lib.kv_prefill_attn.restype = ctypes.c_int
+    lib.kv_prefill_attn.argtypes = [P, I32, P, PD, P, I32, P, P, I32, I32, I32, F, P]
     lib.kv_pack_blocks.restype = ctypes.c_int
     lib.kv_pack_blocks.argtypes = [P, PD, P, I64, P]
     lib.kv_restore_blocks.restype = ctypes.c_int
@@ -144,6 +146,17 @@ def kv_decode_attn(out, q, pool, block_table, context_lens, max_context_len, sca
         _ptr(out), out_dtype, _ptr(q), ctypes.byref(pool_desc(pool)), _ptr(block_table),
         block_table.shape[1], _ptr(context_lens), batch, num_q_heads, int(max_context_len),
         float(scale), int(num_workgroups), _ptr(workspace), ws_bytes, _stream_handle(stream)))
+
+
+def kv_prefill_attn(out, q, pool, block_table, context_lens, q_starts, max_q_len, scale, stream=None) -> None:
+    """Enqueue causal attention of the packed query tokens ``q`` ([T][Hq][D]) over the pool; ``out`` is
+    written in place ([T][Hq][D], bf16 or fp32)."""
+    _, num_q_heads, _ = q.shape
+    out_dtype = {torch.bfloat16: KV_DTYPE_BF16, torch.float32: KV_DTYPE_F32}[out.dtype]
+    _check(load().kv_prefill_attn(
+        _ptr(out), out_dtype, _ptr(q), ctypes.byref(pool_desc(pool)), _ptr(block_table),
+        block_table.shape[1], _ptr(context_lens), _ptr(q_starts), context_lens.numel(), num_q_heads,
+        int(max_q_len), float(scale), _stream_handle(stream)))
 
 
 def kv_pack_blocks(replica, pool, block_ids, n=None, stream=None) -> None:

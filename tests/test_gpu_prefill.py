@@ -1,0 +1,151 @@
+"""GPU parity of kv_prefill_attn (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as U
+from paper_2601_22438_amd import kvflow
+from paper_2601_22438_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+class DevicePrefill:
+    def __init__(self, case: W.PrefillCase, pool=None):
+        self.case = case
+        kv = case.kv
+        self.q = U.bf16_tensor(case.q) if case.total_q else torch.empty((0,) + case.q.shape[1:],
+                                                                        dtype=torch.bfloat16, device="cuda")
+        self.pool = U.bf16_tensor(kv.pool) if pool is None else pool
+        self.block_table = torch.from_numpy(kv.block_table).cuda()
+        self.context_lens = torch.from_numpy(kv.context_lens).cuda()
+        self.q_starts = torch.from_numpy(case.q_starts).cuda()
+
+    def run(self, out_dtype=torch.float32, canary_rows=3, max_q_len=None, block_table=None, pool=None):
+        c, g = self.case, self.case.geom
+        # rows after the last packed query token must stay untouched
+        out = torch.full((c.total_q + canary_rows, g.num_q_heads, g.head_dim), float("nan"),
+                         dtype=out_dtype, device="cuda")
+        kvflow.kv_prefill_attn(out, self.q, self.pool if pool is None else pool,
+                               self.block_table if block_table is None else block_table, self.context_lens,
+                               self.q_starts, c.max_q_len if max_q_len is None else max_q_len, float(g.scale))
+        torch.cuda.synchronize()
+        assert torch.isnan(out[c.total_q:].float()).all(), "wrote past the last query row"
+        return out[:c.total_q]
+
+
+def oracle_out(oracle, case, rows=None):
+    kv = case.kv
+    return oracle.prefill_attn(case.q, kv.pool, kv.block_table, kv.context_lens, case.q_starts, case.geom.scale,
+                               rows=rows)
+
+
+def test_prefill_tiny_matches_oracle(oracle):
+    case = W.prefill_tiny()
+    want = oracle_out(oracle, case)
+    dev = DevicePrefill(case)
+    U.assert_close_to_oracle(dev.run(torch.float32), want, "fp32 out")
+    got16 = dev.run(torch.bfloat16)
+    # bf16 output: the fp32 result rounded once more
+    err = np.abs(got16.double().cpu().numpy() - want)
+    assert err.max() <= U.MAX_ABS + 2.0 ** -8 * np.abs(want).max()
+
+
+# (Hq, Hkv, D, bs): groups of 1, 2, 3, 4, 8 and 16 query heads per KV head, both head sizes and block sizes
+@pytest.mark.parametrize("geom", [(4, 4, 128, 16), (4, 2, 64, 32), (6, 2, 64, 16), (8, 2, 128, 32),
+                                  (16, 2, 128, 16), (16, 1, 64, 16)])
+def test_geometries_and_ragged_lengths(oracle, geom):
+    Hq, Hkv, D, bs = geom
+    g = W.Geometry(Hq, Hkv, D, bs)
+    lens = np.array([1, 31, 32, 33, 97, 300, 200, 129], np.int32)
+    q_lens = np.array([1, 31, 5, 33, 64, 300, 65, 128], np.int32)
+    case = W.make_prefill_case("geom", 40 + Hq, g, lens, q_lens, max_blocks_per_seq=-(-300 // bs), dirty="last")
+    U.assert_close_to_oracle(DevicePrefill(case).run(), oracle_out(oracle, case), str(geom))
+
+
+def test_single_query_per_sequence_is_the_decode_result(oracle):
+    g = W.Geometry(32, 8, 128, 16)
+    lens = np.array([700, 33, 1, 256], np.int32)
+    case = W.make_prefill_case("as_decode", 51, g, lens, np.ones(4, np.int32), max_blocks_per_seq=64, dirty="last")
+    got = DevicePrefill(case).run()
+    want = oracle.decode_attn(case.q, case.kv.pool, case.kv.block_table, case.kv.context_lens, g.scale)
+    U.assert_close_to_oracle(got, want, "q_len 1")
+
+
+def test_sequences_without_queries_and_empty_batch(oracle):
+    g = W.Geometry(8, 2, 64, 16)
+    lens = np.array([40, 0, 77], np.int32)
+    case = W.make_prefill_case("gaps", 52, g, lens, np.array([0, 0, 50], np.int32), max_blocks_per_seq=8,
+                               dirty="last")
+    U.assert_close_to_oracle(DevicePrefill(case).run(), oracle_out(oracle, case), "gaps")
+    none = W.make_prefill_case("none", 53, g, lens, np.zeros(3, np.int32), max_blocks_per_seq=8, dirty="last")
+    assert DevicePrefill(none).run().shape[0] == 0
+
+
+def test_more_queries_than_cached_tokens_gives_zero_rows(oracle):
+    """Outside the normal contract (q_len <= context length) the excess queries see no key."""
+    g = W.Geometry(8, 2, 64, 16)
+    case = W.make_prefill_case("excess", 54, g, np.array([70, 20], np.int32), np.array([70, 20], np.int32),
+                               max_blocks_per_seq=8, dirty="last")
+    kv = case.kv
+    # sequence 1 now claims only 12 cached tokens for its 20 queries; sequence 0 none at all
+    kv.context_lens[:] = [0, 12]
+    want = oracle_out(oracle, case)
+    assert np.array_equal(want[:70 + 8], np.zeros_like(want[:78]))
+    U.assert_close_to_oracle(DevicePrefill(case).run(), want, "excess")
+
+
+def test_result_depends_only_on_logical_positions(oracle):
+    """Same blocks under other physical ids, garbage in every unreferenced slot: bitwise equal output."""
+    case = W.prefill_tiny(seed=55)
+    kv, g = case.kv, case.geom
+    base = DevicePrefill(case).run()
+    rng = np.random.default_rng(56)
+    perm = rng.permutation(kv.num_blocks).astype(np.int32)
+    pool2 = np.full_like(kv.pool, 0x7FC0)                             # NaN patterns everywhere
+    pool2[perm] = kv.pool
+    table2 = np.where(kv.block_table >= 0, perm[np.maximum(kv.block_table, 0)], -1).astype(np.int32)
+    for b, L in enumerate(kv.context_lens):                            # slots past the end of the last block: NaN
+        if L % g.block_size:
+            pool2[table2[b, L // g.block_size], :, :, L % g.block_size:, :] = 0x7FC0
+    used = np.zeros(kv.num_blocks, bool)
+    for b, L in enumerate(kv.context_lens):
+        used[table2[b, :-(-int(L) // g.block_size)]] = True
+    pool2[~used] = 0x7FC0
+    got = DevicePrefill(case, pool=U.bf16_tensor(pool2)).run(block_table=torch.from_numpy(table2).cuda())
+    assert torch.equal(base, got)
+
+
+def test_grid_bound_larger_than_needed_changes_nothing(oracle):
+    case = W.prefill_tiny(seed=57)
+    dev = DevicePrefill(case)
+    assert torch.equal(dev.run(), dev.run(max_q_len=case.max_q_len + 1000))
+
+
+def test_recompute_shrunk_matches_oracle_on_every_row(oracle):
+    case = W.recompute(shrink=16)
+    U.assert_close_to_oracle(DevicePrefill(case).run(), oracle_out(oracle, case), "recompute/16")
+
+
+def sample_rows(case, n_rows, seed):
+    """First and last query of every sequence for a few heads, plus uniformly drawn (token, head) pairs."""
+    rng = np.random.default_rng(seed)
+    Hq = case.geom.num_q_heads
+    rows = []
+    for b in range(case.batch):
+        if case.q_lens[b]:
+            rows += [(int(case.q_starts[b]), 0), (int(case.q_starts[b + 1]) - 1, Hq - 1)]
+    t = rng.integers(0, case.total_q, n_rows)
+    h = rng.integers(0, Hq, n_rows)
+    rows += list(zip(t.tolist(), h.tolist()))
+    return np.array(rows, np.int32)
+
+
+@pytest.mark.parametrize("maker", [W.recompute, W.chunked_recompute])
+def test_full_size_cases_on_sampled_rows(oracle, maker):
+    case = maker()
+    rows = sample_rows(case, 200, 58)
+    want = oracle_out(oracle, case, rows=rows)
+    got = DevicePrefill(case).run(torch.float32, canary_rows=1)
+    pick = got[torch.from_numpy(rows[:, 0].astype(np.int64)).cuda(), torch.from_numpy(rows[:, 1].astype(np.int64)).cuda()]
+    U.assert_close_to_oracle(pick, want, case.name)

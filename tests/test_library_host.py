@@ -155,3 +155,17 @@ def test_fp8_pool_descriptor_checks(lib):
         assert decode(lib, kvflow, bad, hq=32) == -2
     assert decode(lib, kvflow, kvflow.kv_pool_desc(0x10000, 8, 8, 16, 128, 3, 1.0, 1.0), hq=32) == -3
     assert lib.kv_block_bytes(ctypes.byref(kvflow.kv_pool_desc(0x10000, 8, 8, 16, 128, 3, 1.0, 1.0))) == 0
+
+
+def test_prefill_rejects_bad_arguments_before_any_launch(lib):
+    from paper_2601_22438_amd import kvflow
+    ok = desc(kvflow)
+    pf = lambda p=ok, out=0x20000, q=0x30000, tb=0x40000, mb=4, lens=0x50000, qs=0x60000, b=2, hq=8, mq=64, od=1: \
+        lib.kv_prefill_attn(out, od, q, ctypes.byref(p), tb, mb, lens, qs, b, hq, mq, 0.125, None)
+    assert pf(b=0) == 0 and pf(mq=0) == 0                                         # nothing to do
+    assert pf(out=0) == -1 and pf(q=0) == -1 and pf(tb=0) == -1 and pf(lens=0) == -1 and pf(qs=0) == -1
+    assert pf(p=desc(kvflow, base=0)) == -1
+    assert pf(b=-1) == -2 and pf(mq=-1) == -2 and pf(mb=0) == -2 and pf(hq=7) == -2
+    assert pf(p=desc(kvflow, d=96)) == -3 and pf(od=2) == -3 and pf(b=65536) == -3
+    assert pf(p=kvflow.kv_pool_desc(0x10000, 8, 2, 16, 64, 2, 0.25, 0.25)) == -3  # FP8 pool
+    assert pf(out=0x20008) == -4 and pf(q=0x30004) == -4
