@@ -123,11 +123,12 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 
     // ---- global -> LDS staging of K/V tiles
     const int bs = p.block_size;
-    const int64_t head_elems = (int64_t)bs * D;
-    const int64_t v_off = (int64_t)p.num_kv_heads * head_elems;
-    const int64_t blk_elems = 2 * v_off;
+    const uint32_t head_bytes = (uint32_t)bs * D * 2;
+    const uint32_t v_bytes = (uint32_t)p.num_kv_heads * head_bytes;   // K -> V within a block
+    const uint32_t blk_bytes = 2 * v_bytes;
     const int r = tid / S::kLanesPerRow, c = tid % S::kLanesPerRow;
     const int32_t* trow = table_ptr + (int64_t)b * p.max_blocks_per_seq;
+    const char* lane_base = (const char*)pool_ptr + (uint64_t)kvh * head_bytes + c * 16;
     // rows past the last cached token are read from the last token's row (always mapped) and masked
     auto load_ids = [&](int t, int (&ids)[S::kPasses]) {
 #pragma unroll
@@ -141,18 +142,20 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
         for (int ps = 0; ps < S::kPasses; ++ps) {
             const int kp = min(kTileTokens * t + r + ps * S::kRowsPerPass, L - 1);
-            const uint16_t* src = pool_ptr + (int64_t)ids[ps] * blk_elems + (int64_t)kvh * head_elems +
-                                  (int64_t)(kp & (bs - 1)) * D + c * 8;
+            const uint32_t row_off = (uint32_t)(kp & (bs - 1)) * (D * 2);
+            const char* src = lane_base + ((uint64_t)(uint32_t)ids[ps] * blk_bytes + row_off);
             kg[ps] = *(const u32x4*)src;
-            vg[ps] = *(const u32x4*)(src + v_off);
+            vg[ps] = *(const u32x4*)(src + v_bytes);
         }
     };
     auto lstore = [&](int t, unsigned char* buf) {
+        const bool ragged = kTileTokens * t + kTileTokens > L;       // wave-uniform, last tile only
 #pragma unroll
         for (int ps = 0; ps < S::kPasses; ++ps) {
             const int rr = r + ps * S::kRowsPerPass;
             // V rows past the end are zeroed: 0 * NaN must not reach the sum
-            const u32x4 v = kTileTokens * t + rr < L ? vg[ps] : u32x4{0u, 0u, 0u, 0u};
+            u32x4 v = vg[ps];
+            if (ragged && kTileTokens * t + rr >= L) v = u32x4{0u, 0u, 0u, 0u};
             *(u32x4*)(buf + rr * S::kKPitch + c * 16) = kg[ps];
             *(u32x4*)(buf + S::kKBytes + rr * S::kVPitch + c * 16) = v;
         }
@@ -182,8 +185,9 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     // transposed V read: lanes 4e+c of a 16-lane group point at row 4g+e, channels 4c..4c+3 of a d-tile
     const int v_off_lds = S::kKBytes + (4 * g + (j >> 2)) * S::kVPitch + (j & 3) * 8;
 
-    auto compute = [&](int t, const unsigned char* buf, auto masked_tag) {
-        constexpr bool masked = decltype(masked_tag)::value;
+    auto compute = [&](int t, const unsigned char* buf) {
+        // only the tiles on the diagonal reach past the wavefront's first query (wave-uniform)
+        const bool masked = kTileTokens * t + kTileTokens - 1 > pa;
         // ---- S^T = K Q^T, two 16-key subtiles
         f32x4 s[NQB][2];
 #pragma unroll
@@ -208,11 +212,19 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float x = s[qb][u][i] * p.scale_log2e;
-                    if (masked && kTileTokens * t + 16 * u + 4 * g + i > qvis[qb]) x = -INFINITY;
-                    tt[qb][4 * u + i] = x;
-                }
+                for (int i = 0; i < 4; ++i) tt[qb][4 * u + i] = s[qb][u][i] * p.scale_log2e;
+        }
+        if (masked) {
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (kTileTokens * t + 16 * u + 4 * g + i > qvis[qb]) tt[qb][4 * u + i] = -INFINITY;
+        }
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
             mx[qb] = fmaxf(fmaxf(fmaxf(tt[qb][0], tt[qb][1]), fmaxf(tt[qb][2], tt[qb][3])),
                            fmaxf(fmaxf(tt[qb][4], tt[qb][5]), fmaxf(tt[qb][6], tt[qb][7])));
             raise |= mx[qb] > m_run[qb] + kMaxSlack;
@@ -275,10 +287,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         lstore(t + 1, nxt);
         gload(t + 2, ids);
         load_ids(t + 3, ids);
-        if (t <= tl) {
-            if (kTileTokens * t + kTileTokens - 1 > pa) compute(t, cur, std::true_type{});
-            else compute(t, cur, std::false_type{});
-        }
+        if (t <= tl) compute(t, cur);
         __syncthreads();
     }
 
