@@ -176,6 +176,8 @@ int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_d
     if (rc != KV_OK) return rc;
     if (batch < 0 || num_q_heads <= 0 || max_blocks_per_seq <= 0 || max_q_len < 0) return KV_ERR_SHAPE;
     if (num_q_heads % pool->num_kv_heads) return KV_ERR_SHAPE;
+    // the kernel takes the max of raw scores before scaling them
+    if (!(scale > 0.f) || !std::isfinite(scale)) return KV_ERR_SHAPE;
     if (pool->dtype != KV_DTYPE_BF16) return KV_ERR_UNSUPPORTED;
     if (out_dtype != KV_DTYPE_BF16 && out_dtype != KV_DTYPE_F32) return KV_ERR_UNSUPPORTED;
     if (batch > 65535 || num_q_heads > 65535) return KV_ERR_UNSUPPORTED;
@@ -196,7 +198,7 @@ int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_d
     p.num_q_heads = num_q_heads;
     p.num_kv_heads = pool->num_kv_heads;
     p.group = group;
-    p.heads_per_wg = group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+    p.heads_per_wg = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
     p.block_size = pool->block_size;
     p.block_shift = pool->block_size == 16 ? 4 : 5;
     p.out_f32 = out_dtype == KV_DTYPE_F32;

@@ -44,8 +44,8 @@ hipError_t launch_decode(const DecodeParams& p, int head_dim, int workgroups, hi
 hipError_t launch_decode_fp8(const DecodeParams& p, int head_dim, int workgroups, hipStream_t stream);
 constexpr int kFp8TileTokens = 64;
 
-// Prefill (recomputation): a workgroup is 4 wavefronts, each owning 16 * kPrefillQueryBlocks query rows.
-constexpr int kPrefillWaves = 4;
+// Prefill (recomputation): a workgroup is 8 wavefronts, each owning 16 * kPrefillQueryBlocks query rows.
+constexpr int kPrefillWaves = 8;
 constexpr int kPrefillThreads = kPrefillWaves * 64;
 constexpr int kPrefillQueryBlocks = 2;
 
@@ -58,10 +58,10 @@ struct PrefillParams {
     const int32_t* q_starts;   // [batch + 1]
     int32_t max_blocks_per_seq;
     int32_t batch, num_q_heads, num_kv_heads, group;
-    int32_t heads_per_wg;      // 4, 2 or 1 query heads of one group per workgroup (divides group)
+    int32_t heads_per_wg;      // 8, 4, 2 or 1 query heads of one group per workgroup (divides group)
     int32_t block_size, block_shift;
     int32_t out_f32;
-    float scale_log2e;
+    float scale_log2e;         // scale * log2(e), > 0
 };
 
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int max_q_len, hipStream_t stream);

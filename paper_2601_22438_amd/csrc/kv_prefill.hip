@@ -4,17 +4,20 @@
 // already; query j sits at position context_len - q_len + j and sees keys 0 .. its position.
 //
 // This is a dense contraction (4 * head_dim flops per (query, key) pair), bound by the matrix
-// cores, not by HBM.  A workgroup of 4 wavefronts walks the keys of one (sequence, KV head) in
-// 32-token tiles that it stages in LDS once (double-buffered, next tile's global loads in
-// flight) and that all 4 wavefronts consume.  Each wavefront owns 16 * NQB query rows: query
-// tokens of one query head, so the 4 wavefronts are the 4 query heads of a group over the same
-// token range when the group allows it (same causal extent, K/V shared), else neighbouring token
-// ranges.  Per tile and wavefront, in the same transposed orientation as the decode kernel:
+// cores, not by HBM.  A workgroup of 8 wavefronts (two per SIMD) walks the keys of one
+// (sequence, KV head) in 32-token tiles that it stages in LDS once (a ring of four stages, later
+// tiles' global loads in flight) and that all wavefronts consume.  Each wavefront owns 16 * NQB
+// query rows: query tokens of one query head, so the wavefronts are the query heads of a group
+// over the same token range when the group allows it (same causal extent, K/V shared), else
+// neighbouring token ranges.  Per tile and wavefront, in the same transposed orientation as the
+// decode kernel:
 //     S^T[key][query] = K[key][d] * Q^T[d][query]          (v_mfma_f32_16x16x32_bf16)
 //     O^T[d][query]  += V^T[d][key] * P^T[key][query]
 // so a lane's softmax statistics belong to one query (lane % 16), P leaves the first product in
 // the layout the second one wants, Q stays in registers for the whole kernel and every K/V
-// fragment read from LDS serves NQB MFMAs.
+// fragment read from LDS serves NQB MFMAs.  The loop is software-pipelined: while the vector ALU
+// turns tile t's scores into probabilities the matrix core forms tile t + 1's scores, and the K
+// fragments of tile t + 2 and the V fragments of tile t are read from LDS a phase before use.
 //
 // Grid: x = query-head group (fastest, so that with 8 or more groups the workgroups that read
 // one KV head's tiles land on one XCD and share its L2), y = token range, heaviest (latest)
@@ -29,17 +32,18 @@ struct PrefillShape {
     static constexpr int kSteps = D / 32;                 // MFMA k-steps over the head dimension
     static constexpr int kDTiles = D / 16;                // 16-channel output tiles
     static constexpr int kLanesPerRow = D / 8;            // lanes covering one K/V row with 16-byte loads
-    static constexpr int kRowsPerPass = kPrefillThreads / kLanesPerRow;
-    static constexpr int kPasses = kTileTokens / kRowsPerPass;
+    static constexpr int kLoaders = kTileTokens * kLanesPerRow;   // threads that stage a tile, one row chunk each
+    static_assert(kLoaders <= kPrefillThreads && kLoaders % 64 == 0, "whole wavefronts stage the tile");
     static constexpr int kKPitch = D * 2 + 16;            // LDS row pitches in bytes: 16 rows read by 16 lanes
     static constexpr int kVPitch = D * 2 + 32;            // (K) / transposed 4x16 reads (V) hit distinct banks
     static constexpr int kKBytes = kTileTokens * kKPitch;
     static constexpr int kVBytes = kTileTokens * kVPitch;
     static constexpr int kStage = kKBytes + kVBytes;
+    static constexpr int kRing = 4;
+    static constexpr int kLdsBytes = kRing * kStage;
 };
 
-// Register budget of 2 wavefronts per SIMD (8 per compute unit, two workgroups): while one wavefront
-// of a SIMD is in its softmax (vector ALU) the other can keep the matrix core busy.
+// Register budget of 2 wavefronts per SIMD: the 8 wavefronts of a workgroup fill a compute unit.
 template <int D, int NQB>
 __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(
     const PrefillParams p, const uint16_t* __restrict__ q_ptr, const uint16_t* __restrict__ pool_ptr,
@@ -49,7 +53,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     using S = PrefillShape<D>;
     constexpr int QW = 16 * NQB;                          // query rows per wavefront
     static_assert(kTileTokens == 32, "tile indices below are positions >> 5");
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * S::kStage];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // S::kLdsBytes
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -127,57 +131,53 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     const uint32_t v_bytes = (uint32_t)p.num_kv_heads * head_bytes;   // K -> V within a block
     const uint32_t blk_bytes = 2 * v_bytes;
     const int r = tid / S::kLanesPerRow, c = tid % S::kLanesPerRow;
+    const bool loader = tid < S::kLoaders;                // wave-uniform: stages row r, 16-byte chunk c
     const int32_t* trow = table_ptr + (int64_t)b * p.max_blocks_per_seq;
     const char* lane_base = (const char*)pool_ptr + (uint64_t)kvh * head_bytes + c * 16;
     // rows past the last cached token are read from the last token's row (always mapped) and masked
-    auto load_ids = [&](int t, int (&ids)[S::kPasses]) {
-#pragma unroll
-        for (int ps = 0; ps < S::kPasses; ++ps) {
-            const int kp = min(kTileTokens * t + r + ps * S::kRowsPerPass, L - 1);
-            ids[ps] = trow[kp >> p.block_shift];
-        }
+    auto load_id = [&](int t) -> int {
+        int id = 0;
+        if (loader) id = trow[min(kTileTokens * t + r, L - 1) >> p.block_shift];
+        return id;
     };
-    u32x4 kg[S::kPasses], vg[S::kPasses];
-    auto gload = [&](int t, const int (&ids)[S::kPasses]) {
-#pragma unroll
-        for (int ps = 0; ps < S::kPasses; ++ps) {
-            const int kp = min(kTileTokens * t + r + ps * S::kRowsPerPass, L - 1);
+    u32x4 kg = {0u, 0u, 0u, 0u}, vg = {0u, 0u, 0u, 0u};
+    auto gload = [&](int t, int id) {
+        if (loader) {
+            const int kp = min(kTileTokens * t + r, L - 1);
             const uint32_t row_off = (uint32_t)(kp & (bs - 1)) * (D * 2);
-            const char* src = lane_base + ((uint64_t)(uint32_t)ids[ps] * blk_bytes + row_off);
-            kg[ps] = *(const u32x4*)src;
-            vg[ps] = *(const u32x4*)(src + v_bytes);
+            const char* src = lane_base + ((uint64_t)(uint32_t)id * blk_bytes + row_off);
+            kg = *(const u32x4*)src;
+            vg = *(const u32x4*)(src + v_bytes);
         }
     };
+    const int lds_k_off = r * S::kKPitch + c * 16, lds_v_off = S::kKBytes + r * S::kVPitch + c * 16;
     auto lstore = [&](int t, unsigned char* buf) {
-        const bool ragged = kTileTokens * t + kTileTokens > L;       // wave-uniform, last tile only
-#pragma unroll
-        for (int ps = 0; ps < S::kPasses; ++ps) {
-            const int rr = r + ps * S::kRowsPerPass;
+        if (loader) {
             // V rows past the end are zeroed: 0 * NaN must not reach the sum
-            u32x4 v = vg[ps];
-            if (ragged && kTileTokens * t + rr >= L) v = u32x4{0u, 0u, 0u, 0u};
-            *(u32x4*)(buf + rr * S::kKPitch + c * 16) = kg[ps];
-            *(u32x4*)(buf + S::kKBytes + rr * S::kVPitch + c * 16) = v;
+            u32x4 v = vg;
+            if (kTileTokens * t + r >= L) v = u32x4{0u, 0u, 0u, 0u};
+            *(u32x4*)(buf + lds_k_off) = kg;
+            *(u32x4*)(buf + lds_v_off) = v;
         }
     };
 
-    // ---- Q^T fragments: query column j of block qb, channels 32ks + 8g .. +7
+    // ---- Q^T fragments: query column j of block qb, channels 32ks + 8g .. +7.  Columns past the last
+    //      query re-read the last query's row (in bounds); their results are never stored.  The
+    //      fragments are written by loads and read by MFMAs only, so they may live in either
+    //      register file.
     bf16x8 qreg[NQB][S::kSteps];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-        const uint16_t* qrow = q_ptr + ((int64_t)(qs + qidx[qb]) * p.num_q_heads + head) * D + 8 * g;
+        const uint16_t* qrow = q_ptr + ((int64_t)(qs + min(qidx[qb], n - 1)) * p.num_q_heads + head) * D + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < S::kSteps; ++ks) {
-            u32x4 t = {0u, 0u, 0u, 0u};
-            if (active && qidx[qb] < n) t = *(const u32x4*)(qrow + 32 * ks);
-            qreg[qb][ks] = __builtin_bit_cast(bf16x8, t);
-        }
+        for (int ks = 0; ks < S::kSteps; ++ks) qreg[qb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + 32 * ks));
     }
+    const float sc = p.scale_log2e;                       // > 0
     int qvis[NQB];                                        // last visible key position of the lane's queries
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) qvis[qb] = max(qpos[qb], 0);
 
-    float m_run[NQB], l_run[NQB];
+    float m_run[NQB], l_run[NQB];                         // running max (scaled, log2 domain), lane's share of the denominator
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
@@ -185,48 +185,47 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     // transposed V read: lanes 4e+c of a 16-lane group point at row 4g+e, channels 4c..4c+3 of a d-tile
     const int v_off_lds = S::kKBytes + (4 * g + (j >> 2)) * S::kVPitch + (j & 3) * 8;
 
-    auto compute = [&](int t, const unsigned char* buf) {
-        // only the tiles on the diagonal reach past the wavefront's first query (wave-uniform)
-        const bool masked = kTileTokens * t + kTileTokens - 1 > pa;
-        // ---- S^T = K Q^T, two 16-key subtiles
-        f32x4 s[NQB][2];
+    // K fragments of one tile (two 16-key subtiles): row j of the subtile, channels 32ks + 8g ..
+    bf16x8 kf[2][S::kSteps];
+    auto read_k = [&](const unsigned char* buf) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            bf16x8 kf[S::kSteps];
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int ks = 0; ks < S::kSteps; ++ks)
-                kf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(buf + k_off + u * 16 * S::kKPitch + ks * 64));
+                kf[u][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(buf + k_off + u * 16 * S::kKPitch + ks * 64));
+    };
+    // S^T = K Q^T from the fragments; lane (g, j): s[qb][u][i] is query column j of block qb,
+    // key 32t + 16u + 4g + i
+    auto qk = [&](f32x4 (&s)[NQB][2]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
 #pragma unroll
             for (int qb = 0; qb < NQB; ++qb) s[qb][u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < S::kSteps; ++ks)
 #pragma unroll
                 for (int qb = 0; qb < NQB; ++qb)
-                    s[qb][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qreg[qb][ks], s[qb][u], 0, 0, 0);
+                    s[qb][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[u][ks], qreg[qb][ks], s[qb][u], 0, 0, 0);
         }
-        // ---- online softmax; lane (g, j): s[qb][u][i] is query column j of block qb, key 32t + 16u + 4g + i
-        float tt[NQB][8], mx[NQB];
-        bool raise = false;
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) tt[qb][4 * u + i] = s[qb][u][i] * p.scale_log2e;
-        }
-        if (masked) {
+    };
+    // Fresh scores of tile t: mask what the queries must not see (diagonal tiles only), then make sure
+    // the running max covers them up to the slack; raising it rescales O and the denominator.
+    auto settle = [&](int t, f32x4 (&s)[NQB][2]) {
+        if (kTileTokens * t + kTileTokens - 1 > pa) {                 // wave-uniform
 #pragma unroll
             for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (kTileTokens * t + 16 * u + 4 * g + i > qvis[qb]) tt[qb][4 * u + i] = -INFINITY;
+                        if (kTileTokens * t + 16 * u + 4 * g + i > qvis[qb]) s[qb][u][i] = -INFINITY;
         }
+        float mx[NQB];
+        bool raise = false;
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
-            mx[qb] = fmaxf(fmaxf(fmaxf(tt[qb][0], tt[qb][1]), fmaxf(tt[qb][2], tt[qb][3])),
-                           fmaxf(fmaxf(tt[qb][4], tt[qb][5]), fmaxf(tt[qb][6], tt[qb][7])));
+            mx[qb] = sc * fmaxf(fmaxf(fmaxf(s[qb][0][0], s[qb][0][1]), fmaxf(s[qb][0][2], s[qb][0][3])),
+                               fmaxf(fmaxf(s[qb][1][0], s[qb][1][1]), fmaxf(s[qb][1][2], s[qb][1][3])));
             raise |= mx[qb] > m_run[qb] + kMaxSlack;
         }
         // wave-uniform: does any lane see a score above its query's running max by more than the slack?
@@ -244,50 +243,119 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                 for (int dt = 0; dt < S::kDTiles; ++dt) oacc[qb][dt] *= alpha;
             }
         }
-        bf16x8 pb[NQB];
+    };
+    // probabilities of a settled tile, in the B-operand layout of the second product
+    auto probs = [&](const f32x4 (&s)[NQB][2], bf16x8 (&pb)[NQB]) {
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
             float psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float pe = fast_exp2(tt[qb][e] - m_run[qb]);
+                const float pe = fast_exp2(__builtin_fmaf(s[qb][e >> 2][e & 3], sc, -m_run[qb]));
                 psum += pe;
                 pb[qb][e] = (__bf16)pe;
             }
             l_run[qb] += psum;
         }
-        // ---- O^T += V^T P^T over the tile's 32 keys, one 16-channel tile at a time
+    };
+    // V^T fragments of one tile, one per 16-channel tile: channel row j, keys {4g.., 16 + 4g..}
+    bf16x8 vf[S::kDTiles];
+    auto read_v = [&](const unsigned char* buf) {
 #pragma unroll
         for (int dt = 0; dt < S::kDTiles; ++dt) {
             typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(buf + v_off_lds + dt * 32));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (lds_s16x4_ptr)(buf + v_off_lds + 16 * S::kVPitch + dt * 32));
-            const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb)
-                oacc[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[qb], oacc[qb][dt], 0, 0, 0);
+            vf[dt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     };
+    // O^T += V^T P^T over the tile's 32 keys
+    auto pv = [&](const bf16x8 (&pb)[NQB]) {
+#pragma unroll
+        for (int dt = 0; dt < S::kDTiles; ++dt)
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb)
+                oacc[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pb[qb], oacc[qb][dt], 0, 0, 0);
+    };
 
-    // ---- pipeline: tile t is consumed from buffer t & 1 while tile t + 1 goes registers -> LDS and
-    //      tile t + 2 global -> registers; block ids run one more tile ahead.  One barrier per tile.
-    //      Tiles past the end re-read the last rows (in bounds) and are never consumed.
-    int ids[S::kPasses];
-    load_ids(0, ids);
-    gload(0, ids);
-    load_ids(1, ids);
-    lstore(0, smem);
-    gload(1, ids);
-    load_ids(2, ids);
+    // ---- pipeline over a ring of four LDS stages.  Step t: V fragments of tile t are read; tile t's
+    //      probabilities (vector ALU) overlap tile t + 1's scores (matrix core, K fragments read during
+    //      the step before); then the K fragments of tile t + 2 are read, the second product of tile t
+    //      runs, tile t + 3 goes registers -> LDS, tile t + 4 global -> registers (block id one more
+    //      tile ahead), and tile t + 1's scores are settled.  One barrier per tile.  Tiles past the
+    //      end re-read the last rows (in bounds) and are never consumed.
+    unsigned char* ring[S::kRing];                        // ring[i] holds tile t + i
+#pragma unroll
+    for (int i = 0; i < S::kRing; ++i) ring[i] = smem + i * S::kStage;
+    int id = load_id(0);
+    gload(0, id);
+    id = load_id(1);
+    lstore(0, ring[0]);
+    gload(1, id);
+    id = load_id(2);
+    lstore(1, ring[1]);
+    gload(2, id);
+    id = load_id(3);
+    lstore(2, ring[2]);
+    gload(3, id);
+    id = load_id(4);
     __syncthreads();
-    for (int t = 0; t < nt; ++t) {
-        unsigned char* cur = smem + (t & 1) * S::kStage;
-        unsigned char* nxt = smem + ((t + 1) & 1) * S::kStage;
-        lstore(t + 1, nxt);
-        gload(t + 2, ids);
-        load_ids(t + 3, ids);
-        if (t <= tl) compute(t, cur);
+    auto stage = [&](int t) {                             // part of step t
+        lstore(t + 3, ring[3]);
+        gload(t + 4, id);
+        id = load_id(t + 5);
+    };
+    auto rotate = [&]() {
+        unsigned char* const old = ring[0];
+#pragma unroll
+        for (int i = 0; i + 1 < S::kRing; ++i) ring[i] = ring[i + 1];
+        ring[S::kRing - 1] = old;
+    };
+    f32x4 sa[NQB][2], sb[NQB][2];
+    if (tl >= 0) {
+        read_k(ring[0]);
+        qk(sa);
+        settle(0, sa);
+        read_k(ring[1]);
+    }
+    // a step whose tile has a successor for this wavefront
+    auto step = [&](int t, f32x4 (&s_cur)[NQB][2], f32x4 (&s_next)[NQB][2]) {
+        bf16x8 pb[NQB];
+        read_v(ring[0]);
+        probs(s_cur, pb);
+        qk(s_next);
+        read_k(ring[2]);
+        pv(pb);
+        stage(t);
+        settle(t + 1, s_next);
+        rotate();
+        __syncthreads();
+    };
+    int t = 0;
+    for (; t + 1 < tl; t += 2) {
+        step(t, sa, sb);
+        step(t + 1, sb, sa);
+    }
+    if (t < tl) {
+        step(t, sa, sb);
+        ++t;
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) { sa[qb][0] = sb[qb][0]; sa[qb][1] = sb[qb][1]; }
+    }
+    if (t == tl) {                                        // the wavefront's last tile
+        bf16x8 pb[NQB];
+        read_v(ring[0]);
+        probs(sa, pb);
+        pv(pb);
+        stage(t);
+        rotate();
+        __syncthreads();
+        ++t;
+    }
+    for (; t < nt; ++t) {                                 // other wavefronts of the workgroup go on
+        stage(t);
+        rotate();
         __syncthreads();
     }
 
@@ -312,7 +380,12 @@ static hipError_t launch_prefill_d(const PrefillParams& p, int max_q_len, hipStr
     const dim3 grid((uint32_t)(p.num_q_heads / p.heads_per_wg), (uint32_t)((ranges + tbw - 1) / tbw),
                     (uint32_t)p.batch);
     if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((prefill_kernel<D, NQB>), grid, dim3(kPrefillThreads), 0, stream, p, p.q, p.pool,
+    using S = PrefillShape<D>;
+    // the ring is larger than the 64 KiB a kernel gets without asking
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<D, NQB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((prefill_kernel<D, NQB>), grid, dim3(kPrefillThreads), S::kLdsBytes, stream, p, p.q, p.pool,
                        p.block_table, p.context_lens, p.q_starts, p.out);
     return hipGetLastError();
 }
