@@ -25,6 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core peak
 
 # HBM traffic per decode launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
 # WRITE_SIZE), scaled by the same counters on a plain copy of known size; see profiles/.  Valid
@@ -409,6 +410,37 @@ def bench_llama_layer(args, kvflow, W):
             "note": "working set near the last-level cache size: latency figure, not an HBM measurement"}
 
 
+def bench_recompute(args, kvflow, W):
+    """Recomputation (causal prefill over the paged pool): whole sequences, and a 2048-token chunk over a
+    long restored prefix.  A dense contraction: reported against the bf16 matrix-core peak; flops count the
+    (query, key) pairs inside the causal mask only."""
+    import torch
+    out = {}
+    for maker in (W.recompute, W.chunked_recompute):
+        case = maker()
+        kv, g = case.kv, case.geom
+        q = torch.from_numpy(case.q.view(np.int16)).cuda().view(torch.bfloat16)
+        pool = torch.from_numpy(kv.pool.view(np.int16)).cuda().view(torch.bfloat16)
+        table = torch.from_numpy(kv.block_table).cuda()
+        lens = torch.from_numpy(kv.context_lens).cuda()
+        starts = torch.from_numpy(case.q_starts).cuda()
+        o = torch.empty((case.total_q, g.num_q_heads, g.head_dim), dtype=torch.bfloat16, device="cuda")
+        d = time_calls(lambda: kvflow.kv_prefill_attn(o, q, pool, table, lens, starts, case.max_q_len, float(g.scale)),
+                       20, 5)
+        tflops = case.flops / (d["mean_ms"] * 1e-3) / 1e12
+        out[case.name] = {
+            "context_lens": kv.context_lens.tolist(), "q_lens": case.q_lens.tolist(),
+            "flops_in_mask": case.flops, **d, "TFLOPps": tflops,
+            "roofline": {"bound": "mfma", "kernel": "prefill_kernel<128, 2>", "achieved": tflops,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+                         "traffic": None},
+            "query_tokens_per_s": case.total_q / (d["mean_ms"] * 1e-3),
+        }
+        del q, pool, o
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -487,6 +519,9 @@ def main():
         torch.cuda.empty_cache()
         extra["recovery"] = bench_recovery(args, kvflow, W, args.recovery_blocks)
         log("[bench] recovery done")
+        torch.cuda.empty_cache()
+        extra["recompute"] = bench_recompute(args, kvflow, W)
+        log("[bench] recompute done")
 
     line = {
         "metric": "paged decode KV GB/s (pack/restore GB/s under extra), % of HBM peak, 1 MI355X",

@@ -198,7 +198,8 @@ int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_d
     p.num_q_heads = num_q_heads;
     p.num_kv_heads = pool->num_kv_heads;
     p.group = group;
-    p.heads_per_wg = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+    p.heads_per_wg = kPrefillWaves;
+    while (group % p.heads_per_wg) p.heads_per_wg /= 2;
     p.block_size = pool->block_size;
     p.block_shift = pool->block_size == 16 ? 4 : 5;
     p.out_f32 = out_dtype == KV_DTYPE_F32;
