@@ -449,6 +449,8 @@ def main():
     ap.add_argument("--copy-iters", type=int, default=5)
     ap.add_argument("--recovery-blocks", type=int, default=200_000)
     ap.add_argument("--only-timed", action="store_true", help="skip the extra cases and the CPU baseline")
+    ap.add_argument("--extras", default="replication_mix,long_context_fp8_pool,llama8b_layer,recovery,recompute",
+                    help="comma-separated extra cases to run after the timed workload")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after timing, run one plain device copy of the pool (known size) so that a "
                          "counter-collecting profiler run has a yardstick for FETCH_SIZE / WRITE_SIZE")
@@ -508,20 +510,19 @@ def main():
         main_res.pop(k)
     torch.cuda.empty_cache()
     if not args.only_timed:
-        extra["replication_mix"] = bench_replication_mix(args, kvflow, W)
-        log("[bench] replication_mix done")
-        torch.cuda.empty_cache()
-        extra["long_context_fp8_pool"] = bench_long_context_fp8(args, kvflow, W)
-        log("[bench] long_context_fp8_pool done")
-        torch.cuda.empty_cache()
-        extra["llama8b_layer"] = bench_llama_layer(args, kvflow, W)
-        log("[bench] llama8b_layer done")
-        torch.cuda.empty_cache()
-        extra["recovery"] = bench_recovery(args, kvflow, W, args.recovery_blocks)
-        log("[bench] recovery done")
-        torch.cuda.empty_cache()
-        extra["recompute"] = bench_recompute(args, kvflow, W)
-        log("[bench] recompute done")
+        runners = {
+            "replication_mix": lambda: bench_replication_mix(args, kvflow, W),
+            "long_context_fp8_pool": lambda: bench_long_context_fp8(args, kvflow, W),
+            "llama8b_layer": lambda: bench_llama_layer(args, kvflow, W),
+            "recovery": lambda: bench_recovery(args, kvflow, W, args.recovery_blocks),
+            "recompute": lambda: bench_recompute(args, kvflow, W),
+        }
+        for name in [x for x in args.extras.split(",") if x]:
+            if name not in runners:
+                sys.exit(f"unknown extra case {name!r}; known: {', '.join(runners)}")
+            extra[name] = runners[name]()
+            log(f"[bench] {name} done")
+            torch.cuda.empty_cache()
 
     line = {
         "metric": "paged decode KV GB/s (pack/restore GB/s under extra), % of HBM peak, 1 MI355X",
