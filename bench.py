@@ -416,11 +416,15 @@ def bench_recompute(args, kvflow, W):
     (query, key) pairs inside the causal mask only."""
     import torch
     out = {}
-    for maker in (W.recompute, W.chunked_recompute):
+    for label, maker in (("recompute", W.recompute), ("chunked_recompute", W.chunked_recompute),
+                         ("recompute_fp8_pool", lambda: W.recompute(kv_elt_bytes=1))):
         case = maker()
         kv, g = case.kv, case.geom
         q = torch.from_numpy(case.q.view(np.int16)).cuda().view(torch.bfloat16)
-        pool = torch.from_numpy(kv.pool.view(np.int16)).cuda().view(torch.bfloat16)
+        if kv.pool.dtype == np.uint8:
+            pool = kvflow.Fp8Pool(torch.from_numpy(kv.pool).cuda(), W.FP8_KV_SCALE, W.FP8_KV_SCALE)
+        else:
+            pool = torch.from_numpy(kv.pool.view(np.int16)).cuda().view(torch.bfloat16)
         table = torch.from_numpy(kv.block_table).cuda()
         lens = torch.from_numpy(kv.context_lens).cuda()
         starts = torch.from_numpy(case.q_starts).cuda()
@@ -428,10 +432,11 @@ def bench_recompute(args, kvflow, W):
         d = time_calls(lambda: kvflow.kv_prefill_attn(o, q, pool, table, lens, starts, case.max_q_len, float(g.scale)),
                        20, 5)
         tflops = case.flops / (d["mean_ms"] * 1e-3) / 1e12
-        out[case.name] = {
+        out[label] = {
             "context_lens": kv.context_lens.tolist(), "q_lens": case.q_lens.tolist(),
             "flops_in_mask": case.flops, **d, "TFLOPps": tflops,
-            "roofline": {"bound": "mfma", "kernel": "prefill_kernel<128, 2>", "achieved": tflops,
+            "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<128, 2, {str(kv.pool.dtype == np.uint8).lower()}>",
+                         "achieved": tflops,
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
                          "traffic": None},
             "query_tokens_per_s": case.total_q / (d["mean_ms"] * 1e-3),

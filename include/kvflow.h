@@ -138,12 +138,13 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
  *     s[u]       = scale * sum_d q[t,h,d] * K[table[b][u / bs], kvh, u % bs, d]     0 <= u <= pos
  *     out[t,h,:] = sum_u softmax(s)[u] * V[table[b][u / bs], kvh, u % bs, :]
  * bf16 inputs, fp32 accumulation.  n == 1 is kv_decode_attn's operation.  A query with pos < 0
- * (n > L) sees no key and gives a row of zeros.
+ * (n > L) sees no key and gives a row of zeros.  With an FP8 pool K and V are the stored numbers
+ * times k_scale / v_scale, as for kv_decode_attn.
  *
  *   out            [total_q][num_q_heads][head_dim], out_dtype KV_DTYPE_BF16 or KV_DTYPE_F32, written;
  *                  total_q = q_starts[batch]
  *   q              [total_q][num_q_heads][head_dim] bf16, read; sequences packed in batch order
- *   pool           host struct; bf16 pool, read
+ *   pool           host struct; bf16 or FP8 pool, read
  *   block_table    int32 [batch][max_blocks_per_seq], read; only the first ceil(L/bs) entries of a row
  *   context_lens   int32 [batch], read; counts the query tokens too
  *   q_starts       int32 [batch + 1], read; non-decreasing, q_starts[0] == 0
@@ -151,8 +152,9 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
  * Preconditions on device contents: 0 <= context_lens[b] <= max_blocks_per_seq * bs; table entries as
  * for kv_decode_attn; 0 <= n <= max_q_len.
  * Needs no workspace.  The result depends only on logical token positions.
- * Errors: NULL, SHAPE, UNSUPPORTED (head_dim, block_size, FP8 pool, batch or num_q_heads > 65535,
- * max_q_len > 65535 * 64), ALIGN, LAUNCH.  batch == 0 or max_q_len == 0 returns KV_OK without a launch.
+ * scale must be positive and finite (the kernel takes the max of raw scores before scaling them).
+ * Errors: NULL, SHAPE (also a scale that is not positive and finite), UNSUPPORTED (head_dim, block_size,
+ * dtypes, batch or num_q_heads > 65535, max_q_len > 65535 * 32), ALIGN, LAUNCH.  batch == 0 or max_q_len == 0 returns KV_OK without a launch.
  */
 int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
                     const int32_t* block_table, int32_t max_blocks_per_seq,

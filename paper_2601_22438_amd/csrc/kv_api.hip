@@ -178,7 +178,6 @@ int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_d
     if (num_q_heads % pool->num_kv_heads) return KV_ERR_SHAPE;
     // the kernel takes the max of raw scores before scaling them
     if (!(scale > 0.f) || !std::isfinite(scale)) return KV_ERR_SHAPE;
-    if (pool->dtype != KV_DTYPE_BF16) return KV_ERR_UNSUPPORTED;
     if (out_dtype != KV_DTYPE_BF16 && out_dtype != KV_DTYPE_F32) return KV_ERR_UNSUPPORTED;
     if (batch > 65535 || num_q_heads > 65535) return KV_ERR_UNSUPPORTED;
     if ((int64_t)max_q_len > (int64_t)65535 * 16 * kPrefillQueryBlocks) return KV_ERR_UNSUPPORTED;
@@ -189,7 +188,7 @@ int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_d
     PrefillParams p;
     p.out = out;
     p.q = (const uint16_t*)q;
-    p.pool = (const uint16_t*)pool->base;
+    p.pool = pool->base;
     p.block_table = block_table;
     p.context_lens = context_lens;
     p.q_starts = q_starts;
@@ -203,7 +202,10 @@ int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_d
     p.block_size = pool->block_size;
     p.block_shift = pool->block_size == 16 ? 4 : 5;
     p.out_f32 = out_dtype == KV_DTYPE_F32;
-    p.scale_log2e = (float)((double)scale * 1.4426950408889634074);
+    const bool fp8 = pool->dtype == KV_DTYPE_FP8_E4M3;
+    p.kv_fp8 = fp8;
+    p.scale_log2e = (float)((double)scale * (fp8 ? (double)pool->k_scale : 1.0) * 1.4426950408889634074);
+    p.out_scale = fp8 ? pool->v_scale : 1.f;
     hipError_t e = launch_prefill(p, pool->head_dim, max_q_len, (hipStream_t)stream);
     return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }

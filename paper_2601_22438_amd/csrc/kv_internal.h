@@ -52,7 +52,7 @@ constexpr int kPrefillQueryBlocks = 2;
 struct PrefillParams {
     void* out;                 // [total_q][Hq][D] bf16 or fp32
     const uint16_t* q;         // [total_q][Hq][D] bf16
-    const uint16_t* pool;      // [NB][2][Hkv][bs][D] bf16
+    const void* pool;          // [NB][2][Hkv][bs][D] bf16, or FP8 E4M3 bytes
     const int32_t* block_table;
     const int32_t* context_lens;
     const int32_t* q_starts;   // [batch + 1]
@@ -61,7 +61,9 @@ struct PrefillParams {
     int32_t heads_per_wg;      // 8, 4, 2 or 1 query heads of one group per workgroup (divides group)
     int32_t block_size, block_shift;
     int32_t out_f32;
-    float scale_log2e;         // scale * log2(e), > 0
+    int32_t kv_fp8;
+    float scale_log2e;         // scale * log2(e), times the K scale of an FP8 pool; > 0
+    float out_scale;           // 1, or the V scale of an FP8 pool
 };
 
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int max_q_len, hipStream_t stream);

@@ -44,9 +44,12 @@ struct PrefillShape {
 };
 
 // Register budget of 2 wavefronts per SIMD: the 8 wavefronts of a workgroup fill a compute unit.
-template <int D, int NQB>
+// FP8: the pool holds OCP E4M3 bytes; a staged chunk of 8 elements is 8 bytes in the pool and is widened
+// to bf16 (exactly) on its way into LDS, so everything after the staging is the bf16 path.  The K
+// scale is folded into the score scale, the V scale into the final normalisation.
+template <int D, int NQB, bool FP8>
 __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(
-    const PrefillParams p, const uint16_t* __restrict__ q_ptr, const uint16_t* __restrict__ pool_ptr,
+    const PrefillParams p, const uint16_t* __restrict__ q_ptr, const void* __restrict__ pool_ptr,
     const int32_t* __restrict__ table_ptr, const int32_t* __restrict__ lens_ptr,
     const int32_t* __restrict__ qs_ptr, void* __restrict__ out_ptr)
 {
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
             if (qidx[qb] >= n) continue;
-            const float f = qpos[qb] < 0 ? 0.f : inv[qb];           // a query before position 0 sees nothing
+            const float f = qpos[qb] < 0 ? 0.f : inv[qb] * p.out_scale;   // a query before position 0 sees nothing
             const int64_t row = ((int64_t)(qs + qidx[qb]) * p.num_q_heads + head) * D + 4 * g;
 #pragma unroll
             for (int dt = 0; dt < S::kDTiles; ++dt) {
@@ -127,36 +130,60 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 
     // ---- global -> LDS staging of K/V tiles
     const int bs = p.block_size;
-    const uint32_t head_bytes = (uint32_t)bs * D * 2;
+    constexpr int kElt = FP8 ? 1 : 2;                     // bytes per pool element
+    const uint32_t head_bytes = (uint32_t)bs * D * kElt;
     const uint32_t v_bytes = (uint32_t)p.num_kv_heads * head_bytes;   // K -> V within a block
     const uint32_t blk_bytes = 2 * v_bytes;
     const int r = tid / S::kLanesPerRow, c = tid % S::kLanesPerRow;
-    const bool loader = tid < S::kLoaders;                // wave-uniform: stages row r, 16-byte chunk c
+    const bool loader = tid < S::kLoaders;                // wave-uniform: stages row r, 8-element chunk c
     const int32_t* trow = table_ptr + (int64_t)b * p.max_blocks_per_seq;
-    const char* lane_base = (const char*)pool_ptr + (uint64_t)kvh * head_bytes + c * 16;
+    const char* lane_base = (const char*)pool_ptr + (uint64_t)kvh * head_bytes + c * (8 * kElt);
     // rows past the last cached token are read from the last token's row (always mapped) and masked
     auto load_id = [&](int t) -> int {
         int id = 0;
         if (loader) id = trow[min(kTileTokens * t + r, L - 1) >> p.block_shift];
         return id;
     };
-    u32x4 kg = {0u, 0u, 0u, 0u}, vg = {0u, 0u, 0u, 0u};
+    u32x4 kg = {0u, 0u, 0u, 0u}, vg = {0u, 0u, 0u, 0u};   // FP8: only the first two words are used
     auto gload = [&](int t, int id) {
         if (loader) {
             const int kp = min(kTileTokens * t + r, L - 1);
-            const uint32_t row_off = (uint32_t)(kp & (bs - 1)) * (D * 2);
+            const uint32_t row_off = (uint32_t)(kp & (bs - 1)) * (D * kElt);
             const char* src = lane_base + ((uint64_t)(uint32_t)id * blk_bytes + row_off);
-            kg = *(const u32x4*)src;
-            vg = *(const u32x4*)(src + v_bytes);
+            if (FP8) {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 k2 = *(const u32x2*)src, v2 = *(const u32x2*)(src + v_bytes);
+                kg[0] = k2.x; kg[1] = k2.y;
+                vg[0] = v2.x; vg[1] = v2.y;
+            } else {
+                kg = *(const u32x4*)src;
+                vg = *(const u32x4*)(src + v_bytes);
+            }
         }
+    };
+    // 8 E4M3 bytes (two words) -> 8 bf16, element order kept
+    auto widen = [](u32x4 raw) -> u32x4 {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        bf16x8 o;
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], false);
+            const f32x2 b2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], true);
+            o[4 * w + 0] = (__bf16)a.x;
+            o[4 * w + 1] = (__bf16)a.y;
+            o[4 * w + 2] = (__bf16)b2.x;
+            o[4 * w + 3] = (__bf16)b2.y;
+        }
+        return __builtin_bit_cast(u32x4, o);
     };
     const int lds_k_off = r * S::kKPitch + c * 16, lds_v_off = S::kKBytes + r * S::kVPitch + c * 16;
     auto lstore = [&](int t, unsigned char* buf) {
         if (loader) {
             // V rows past the end are zeroed: 0 * NaN must not reach the sum
-            u32x4 v = vg;
+            u32x4 k = kg, v = vg;
+            if (FP8) { k = widen(k); v = widen(v); }
             if (kTileTokens * t + r >= L) v = u32x4{0u, 0u, 0u, 0u};
-            *(u32x4*)(buf + lds_k_off) = kg;
+            *(u32x4*)(buf + lds_k_off) = k;
             *(u32x4*)(buf + lds_v_off) = v;
         }
     };
@@ -177,9 +204,15 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) qvis[qb] = max(qpos[qb], 0);
 
-    float m_run[NQB], l_run[NQB];                         // running max (scaled, log2 domain), lane's share of the denominator
+    // Running max (scaled, log2 domain) and denominator.  The denominator is one more row block of
+    // the second product (a block of ones in place of V^T): it sums the same bf16-rounded
+    // probabilities as the numerator (a single visible key gives exactly its V row) and every entry
+    // of l_acc[qb] is the full sum for the lane's query, with no cross-lane reduction.
+    float m_run[NQB];
+    f32x4 l_acc[NQB];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_acc[qb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
 
     const int k_off = j * S::kKPitch + 16 * g;            // K operand: row j, channels 8g ..
     // transposed V read: lanes 4e+c of a 16-lane group point at row 4g+e, channels 4c..4c+3 of a d-tile
@@ -238,7 +271,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                 // tile 0 holds key 0, visible to every query, so m_new is finite from the first tile on
                 const float alpha = fast_exp2(m_run[qb] - m_new);
                 m_run[qb] = m_new;
-                l_run[qb] *= alpha;
+                l_acc[qb] *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < S::kDTiles; ++dt) oacc[qb][dt] *= alpha;
             }
@@ -247,16 +280,10 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     // probabilities of a settled tile, in the B-operand layout of the second product
     auto probs = [&](const f32x4 (&s)[NQB][2], bf16x8 (&pb)[NQB]) {
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-            float psum = 0.f;
+        for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float pe = fast_exp2(__builtin_fmaf(s[qb][e >> 2][e & 3], sc, -m_run[qb]));
-                psum += pe;
-                pb[qb][e] = (__bf16)pe;
-            }
-            l_run[qb] += psum;
-        }
+            for (int e = 0; e < 8; ++e)
+                pb[qb][e] = (__bf16)fast_exp2(__builtin_fmaf(s[qb][e >> 2][e & 3], sc, -m_run[qb]));
     };
     // V^T fragments of one tile, one per 16-channel tile: channel row j, keys {4g.., 16 + 4g..}
     bf16x8 vf[S::kDTiles];
@@ -272,6 +299,9 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     };
     // O^T += V^T P^T over the tile's 32 keys
     auto pv = [&](const bf16x8 (&pb)[NQB]) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+            l_acc[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[qb], l_acc[qb], 0, 0, 0);
 #pragma unroll
         for (int dt = 0; dt < S::kDTiles; ++dt)
 #pragma unroll
@@ -362,16 +392,12 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     if (active) {
         float inv[NQB];
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-            float l = l_run[qb] + __shfl_xor(l_run[qb], 16);
-            l += __shfl_xor(l, 32);
-            inv[qb] = 1.f / l;
-        }
+        for (int qb = 0; qb < NQB; ++qb) inv[qb] = 1.f / l_acc[qb][0];
         store_rows(oacc, inv);
     }
 }
 
-template <int D>
+template <int D, bool FP8>
 static hipError_t launch_prefill_d(const PrefillParams& p, int max_q_len, hipStream_t stream)
 {
     constexpr int NQB = kPrefillQueryBlocks;
@@ -382,18 +408,20 @@ static hipError_t launch_prefill_d(const PrefillParams& p, int max_q_len, hipStr
     if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
     using S = PrefillShape<D>;
     // the ring is larger than the 64 KiB a kernel gets without asking
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<D, NQB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<D, NQB, FP8>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsBytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_kernel<D, NQB>), grid, dim3(kPrefillThreads), S::kLdsBytes, stream, p, p.q, p.pool,
-                       p.block_table, p.context_lens, p.q_starts, p.out);
+    hipLaunchKernelGGL((prefill_kernel<D, NQB, FP8>), grid, dim3(kPrefillThreads), S::kLdsBytes, stream, p, p.q,
+                       p.pool, p.block_table, p.context_lens, p.q_starts, p.out);
     return hipGetLastError();
 }
 
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int max_q_len, hipStream_t stream)
 {
-    if (head_dim == 128) return launch_prefill_d<128>(p, max_q_len, stream);
-    if (head_dim == 64) return launch_prefill_d<64>(p, max_q_len, stream);
+    if (head_dim == 128) return p.kv_fp8 ? launch_prefill_d<128, true>(p, max_q_len, stream)
+                                         : launch_prefill_d<128, false>(p, max_q_len, stream);
+    if (head_dim == 64) return p.kv_fp8 ? launch_prefill_d<64, true>(p, max_q_len, stream)
+                                        : launch_prefill_d<64, false>(p, max_q_len, stream);
     return hipErrorInvalidValue;
 }
 

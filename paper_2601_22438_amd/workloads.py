@@ -420,9 +420,9 @@ def prefill_tiny(seed=5) -> PrefillCase:
                              dirty="any", n_dirty=8)
 
 
-def recompute(seed=6, shrink=1, batch=8) -> PrefillCase:
+def recompute(seed=6, shrink=1, batch=8, kv_elt_bytes=2) -> PrefillCase:
     """Whole sequences recomputed after their replicas were dropped: q_len = context length."""
-    g = Geometry(32, 8, 128, 16)
+    g = Geometry(32, 8, 128, 16, kv_elt_bytes)
     lens = _uniform_lens(seed, batch, 2048 // shrink, 8192 // shrink)
     return make_prefill_case("recompute", seed, g, lens, lens, max_blocks_per_seq=512 // shrink, dirty="last")
 

@@ -11,9 +11,11 @@ pytestmark = pytest.mark.gpu
 
 
 class DevicePrefill:
-    def __init__(self, case: W.PrefillCase, pool=None):
+    def __init__(self, case: W.PrefillCase, pool=None, k_scale=1.0, v_scale=1.0):
         self.case = case
         kv = case.kv
+        if pool is None and kv.pool.dtype == np.uint8:
+            pool = U.pool_tensor(kv.pool, k_scale, v_scale)
         self.q = U.bf16_tensor(case.q) if case.total_q else torch.empty((0,) + case.q.shape[1:],
                                                                         dtype=torch.bfloat16, device="cuda")
         self.pool = U.bf16_tensor(kv.pool) if pool is None else pool
@@ -61,6 +63,19 @@ def test_geometries_and_ragged_lengths(oracle, geom):
     q_lens = np.array([1, 31, 5, 33, 64, 300, 65, 128], np.int32)
     case = W.make_prefill_case("geom", 40 + Hq, g, lens, q_lens, max_blocks_per_seq=-(-300 // bs), dirty="last")
     U.assert_close_to_oracle(DevicePrefill(case).run(), oracle_out(oracle, case), str(geom))
+
+
+def test_first_token_returns_its_own_value_row_exactly(oracle):
+    """Position 0 sees one key; numerator and denominator use the same rounded probability."""
+    g = W.Geometry(8, 2, 64, 16)
+    case = W.make_prefill_case("first", 50, g, np.array([40, 7], np.int32), np.array([40, 7], np.int32),
+                               max_blocks_per_seq=4, dirty="last")
+    got = DevicePrefill(case).run().cpu().numpy()
+    v = W.bf16_bits_to_f32(case.kv.pool)
+    for b in range(case.batch):
+        blk = case.kv.block_table[b, 0]
+        for h in range(g.num_q_heads):
+            assert np.array_equal(got[case.q_starts[b], h], v[blk, 1, h // g.group, 0])
 
 
 def test_single_query_per_sequence_is_the_decode_result(oracle):
@@ -149,3 +164,46 @@ def test_full_size_cases_on_sampled_rows(oracle, maker):
     got = DevicePrefill(case).run(torch.float32, canary_rows=1)
     pick = got[torch.from_numpy(rows[:, 0].astype(np.int64)).cuda(), torch.from_numpy(rows[:, 1].astype(np.int64)).cuda()]
     U.assert_close_to_oracle(pick, want, case.name)
+
+
+# ---- FP8 (E4M3) pool: the oracle consumes the same bit patterns and scales
+@pytest.mark.parametrize("geom", [(8, 2, 128, 16), (16, 2, 64, 32), (4, 4, 128, 32)])
+@pytest.mark.parametrize("scales", [(0.25, 0.25), (0.5, 0.125)])
+def test_fp8_pool_geometries_and_scales(oracle, geom, scales):
+    Hq, Hkv, D, bs = geom
+    ks, vs = scales
+    g = W.Geometry(Hq, Hkv, D, bs, kv_elt_bytes=1)
+    lens = np.array([1, 33, 97, 300, 200], np.int32)
+    q_lens = np.array([1, 33, 64, 300, 65], np.int32)
+    case = W.make_prefill_case("fp8geom", 60 + Hq, g, lens, q_lens, max_blocks_per_seq=-(-300 // bs), dirty="last")
+    kv = case.kv
+    want = oracle.prefill_attn(case.q, kv.pool, kv.block_table, kv.context_lens, case.q_starts, g.scale,
+                               k_scale=ks, v_scale=vs)
+    U.assert_close_to_oracle(DevicePrefill(case, k_scale=ks, v_scale=vs).run(), want, f"fp8 {geom} {scales}")
+
+
+def test_fp8_first_token_returns_decoded_v_times_scale_exactly(oracle):
+    g = W.Geometry(8, 2, 128, 16, kv_elt_bytes=1)
+    case = W.make_prefill_case("fp8first", 61, g, np.array([20, 5], np.int32), np.array([20, 5], np.int32),
+                               max_blocks_per_seq=2, dirty="last")
+    kv = case.kv
+    got = DevicePrefill(case, k_scale=0.25, v_scale=0.5).run().cpu().numpy()
+    v = W.fp8_e4m3_bits_to_f32(kv.pool) * np.float32(0.5)
+    for b in range(case.batch):
+        blk = kv.block_table[b, 0]
+        for h in range(g.num_q_heads):
+            assert np.array_equal(got[case.q_starts[b], h], v[blk, 1, h // g.group, 0])
+
+
+def test_fp8_recompute_shrunk_sampled_rows(oracle):
+    base = W.recompute(shrink=4)
+    g = W.Geometry(32, 8, 128, 16, kv_elt_bytes=1)
+    case = W.make_prefill_case("fp8recompute", 62, g, base.kv.context_lens, base.q_lens, max_blocks_per_seq=128,
+                               dirty="last")
+    kv = case.kv
+    rows = sample_rows(case, 300, 63)
+    want = oracle.prefill_attn(case.q, kv.pool, kv.block_table, kv.context_lens, case.q_starts, g.scale, rows=rows,
+                               k_scale=W.FP8_KV_SCALE, v_scale=W.FP8_KV_SCALE)
+    got = DevicePrefill(case, k_scale=W.FP8_KV_SCALE, v_scale=W.FP8_KV_SCALE).run(canary_rows=1)
+    pick = got[torch.from_numpy(rows[:, 0].astype(np.int64)).cuda(), torch.from_numpy(rows[:, 1].astype(np.int64)).cuda()]
+    U.assert_close_to_oracle(pick, want, "fp8 recompute/4")

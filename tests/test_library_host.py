@@ -167,5 +167,8 @@ def test_prefill_rejects_bad_arguments_before_any_launch(lib):
     assert pf(p=desc(kvflow, base=0)) == -1
     assert pf(b=-1) == -2 and pf(mq=-1) == -2 and pf(mb=0) == -2 and pf(hq=7) == -2
     assert pf(p=desc(kvflow, d=96)) == -3 and pf(od=2) == -3 and pf(b=65536) == -3
-    assert pf(p=kvflow.kv_pool_desc(0x10000, 8, 2, 16, 64, 2, 0.25, 0.25)) == -3  # FP8 pool
+    assert pf(p=kvflow.kv_pool_desc(0x10000, 8, 2, 16, 64, 2, 0.0, 0.25)) == -2   # FP8 pool with a bad scale
+    sc = lambda v: lib.kv_prefill_attn(0x20000, 1, 0x30000, ctypes.byref(ok), 0x40000, 4, 0x50000, 0x60000, 2, 8, 64,
+                                       v, None)
+    assert sc(0.0) == -2 and sc(-0.125) == -2 and sc(float("inf")) == -2 and sc(float("nan")) == -2
     assert pf(out=0x20008) == -4 and pf(q=0x30004) == -4

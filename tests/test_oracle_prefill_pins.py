@@ -186,3 +186,22 @@ def test_more_queries_than_context_gives_zero_rows_for_the_excess(oracle):
                               case.geom.scale)
     assert np.array_equal(got[:3], np.zeros_like(got[:3]))
     assert np.array_equal(got[3:], run(oracle, case))
+
+
+def test_fp8_pool_equals_bf16_pool_holding_the_decoded_values(oracle):
+    """E4M3 values times a power-of-two scale are bf16 numbers: both pools must give identical rows."""
+    g = W.Geometry(8, 2, 64, 16, kv_elt_bytes=1)
+    case = W.make_prefill_case("fp8", 33, g, np.array([40, 70], np.int32), np.array([40, 17], np.int32),
+                               num_blocks=16, max_blocks_per_seq=8, dirty="last")
+    kv = case.kv
+    assert kv.pool.dtype == np.uint8
+    ks, vs = 0.25, 0.5
+    dec = W.fp8_e4m3_bits_to_f32(kv.pool)
+    dec[:, 0] *= np.float32(ks)
+    dec[:, 1] *= np.float32(vs)
+    as_bf16 = W.f32_to_bf16_bits(dec)
+    assert np.array_equal(W.bf16_bits_to_f32(as_bf16), dec)          # exactly representable
+    a = oracle.prefill_attn(case.q, kv.pool, kv.block_table, kv.context_lens, case.q_starts, g.scale,
+                            k_scale=ks, v_scale=vs)
+    b = oracle.prefill_attn(case.q, as_bf16, kv.block_table, kv.context_lens, case.q_starts, g.scale)
+    np.testing.assert_allclose(a, b, rtol=1e-15, atol=0)
