@@ -417,7 +417,8 @@ def bench_recompute(args, kvflow, W):
     import torch
     out = {}
     for label, maker in (("recompute", W.recompute), ("chunked_recompute", W.chunked_recompute),
-                         ("recompute_fp8_pool", lambda: W.recompute(kv_elt_bytes=1))):
+                         ("recompute_fp8_pool", lambda: W.recompute(kv_elt_bytes=1)),
+                         ("short_chunk", W.short_chunk_recompute)):
         case = maker()
         kv, g = case.kv, case.geom
         q = torch.from_numpy(case.q.view(np.int16)).cuda().view(torch.bfloat16)
@@ -429,12 +430,16 @@ def bench_recompute(args, kvflow, W):
         lens = torch.from_numpy(kv.context_lens).cuda()
         starts = torch.from_numpy(case.q_starts).cuda()
         o = torch.empty((case.total_q, g.num_q_heads, g.head_dim), dtype=torch.bfloat16, device="cuda")
-        d = time_calls(lambda: kvflow.kv_prefill_attn(o, q, pool, table, lens, starts, case.max_q_len, float(g.scale)),
-                       20, 5)
+        ks = kvflow.kv_prefill_key_splits(case.batch, g.num_q_heads, g.num_kv_heads, case.max_q_len,
+                                          kv.max_context_len)
+        nbytes = kvflow.kv_prefill_workspace_bytes(case.total_q, g.num_q_heads, g.head_dim, ks)
+        ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device="cuda")
+        d = time_calls(lambda: kvflow.kv_prefill_attn(o, q, pool, table, lens, starts, case.max_q_len, float(g.scale),
+                                                      ks, ws), 20, 5)
         tflops = case.flops / (d["mean_ms"] * 1e-3) / 1e12
         out[label] = {
             "context_lens": kv.context_lens.tolist(), "q_lens": case.q_lens.tolist(),
-            "flops_in_mask": case.flops, **d, "TFLOPps": tflops,
+            "flops_in_mask": case.flops, "key_splits": ks, **d, "TFLOPps": tflops,
             "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<128, 2, {str(kv.pool.dtype == np.uint8).lower()}>",
                          "achieved": tflops,
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,

@@ -149,17 +149,38 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
  *   context_lens   int32 [batch], read; counts the query tokens too
  *   q_starts       int32 [batch + 1], read; non-decreasing, q_starts[0] == 0
  *   max_q_len      host-side upper bound of the n above; sizes the grid
+ *   total_q        number of packed query rows (the host's copy of q_starts[batch])
+ *   key_splits     0 or 1: every (sequence, KV head, token range) is walked by one workgroup.  2..16: the key
+ *                  range is cut into that many parts handled by separate workgroups, which fills the chip
+ *                  when there are few query tokens over long contexts; the parts are combined in a fixed
+ *                  order by a second kernel.  kv_prefill_key_splits() suggests a value.
+ *   workspace      only for key_splits > 1: >= kv_prefill_workspace_bytes(...) bytes, 16-byte aligned,
+ *                  scratch (contents on entry ignored, on return unspecified); else may be NULL
  * Preconditions on device contents: 0 <= context_lens[b] <= max_blocks_per_seq * bs; table entries as
- * for kv_decode_attn; 0 <= n <= max_q_len.
- * Needs no workspace.  The result depends only on logical token positions.
+ * for kv_decode_attn; 0 <= n <= max_q_len; q_starts[batch] == total_q.
+ * The result depends only on logical token positions (and on key_splits).
  * scale must be positive and finite (the kernel takes the max of raw scores before scaling them).
  * Errors: NULL, SHAPE (also a scale that is not positive and finite), UNSUPPORTED (head_dim, block_size,
- * dtypes, batch or num_q_heads > 65535, max_q_len > 65535 * 32), ALIGN, LAUNCH.  batch == 0 or max_q_len == 0 returns KV_OK without a launch.
+ * dtypes, batch or num_q_heads > 65535, max_q_len > 65535 * 32), ALIGN, WORKSPACE, LAUNCH (also a grid
+ * of more than 65535 token-range groups x parts).  batch == 0, max_q_len == 0 or total_q == 0 returns
+ * KV_OK without a launch.
  */
 int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
                     const int32_t* block_table, int32_t max_blocks_per_seq,
                     const int32_t* context_lens, const int32_t* q_starts, int32_t batch,
-                    int32_t num_q_heads, int32_t max_q_len, float scale, void* stream);
+                    int32_t num_q_heads, int32_t max_q_len, int64_t total_q, float scale,
+                    int32_t key_splits, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Parts of the key range that fill the chip for these host-side bounds: 1 when the token ranges alone
+ * give enough workgroups, up to 16 otherwise (never parts shorter than 512 keys).  0 on invalid arguments.
+ */
+int32_t kv_prefill_key_splits(int32_t batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t max_q_len,
+                              int32_t max_context_len);
+
+/* Bytes of workspace kv_prefill_attn needs: key_splits records of (head_dim + 4) floats per (query row,
+ * head); 0 for key_splits <= 1 or invalid arguments. */
+size_t kv_prefill_workspace_bytes(int64_t total_q, int32_t num_q_heads, int32_t head_dim, int32_t key_splits);
 
 /*
  * Gather side of block-by-block replication (Sec. 3.2 item 3; meant to run on a

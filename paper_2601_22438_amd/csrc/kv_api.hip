@@ -167,10 +167,39 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
     return KV_OK;
 }
 
+int32_t kv_prefill_key_splits(int32_t batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t max_q_len,
+                              int32_t max_context_len)
+{
+    if (batch <= 0 || num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads || max_q_len <= 0 ||
+        max_context_len <= 0)
+        return 0;
+    const int32_t group = num_q_heads / num_kv_heads;
+    int32_t hpw = kPrefillWaves;
+    while (group % hpw) hpw /= 2;
+    const int64_t ranges = ((int64_t)max_q_len + 16 * kPrefillQueryBlocks - 1) / (16 * kPrefillQueryBlocks);
+    const int64_t tbw = kPrefillWaves / hpw;
+    const int64_t wgs = (int64_t)(num_q_heads / hpw) * ((ranges + tbw - 1) / tbw) * batch;
+    // one workgroup per compute unit and causal ranges of unequal length: below four rounds of
+    // workgroups, cut the key range, but keep parts of >= 16 tiles
+    const int64_t want = (4 * 256 + wgs - 1) / wgs;
+    const int64_t tiles = ((int64_t)max_context_len + kTileTokens - 1) / kTileTokens;
+    int64_t ns = want < tiles / 16 ? want : tiles / 16;
+    if (ns > kPrefillMaxKeySplits) ns = kPrefillMaxKeySplits;
+    return ns < 1 ? 1 : (int32_t)ns;
+}
+
+size_t kv_prefill_workspace_bytes(int64_t total_q, int32_t num_q_heads, int32_t head_dim, int32_t key_splits)
+{
+    if (total_q <= 0 || num_q_heads <= 0 || head_dim <= 0 || key_splits <= 1 || key_splits > kPrefillMaxKeySplits)
+        return 0;
+    return (size_t)key_splits * (size_t)total_q * num_q_heads * (head_dim + kRecordPad) * sizeof(float);
+}
+
 int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
                     const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* context_lens,
                     const int32_t* q_starts, int32_t batch, int32_t num_q_heads, int32_t max_q_len,
-                    float scale, void* stream)
+                    int64_t total_q, float scale, int32_t key_splits, void* workspace, size_t workspace_bytes,
+                    void* stream)
 {
     int rc = check_pool(pool);
     if (rc != KV_OK) return rc;
@@ -181,11 +210,21 @@ int kv_prefill_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_d
     if (out_dtype != KV_DTYPE_BF16 && out_dtype != KV_DTYPE_F32) return KV_ERR_UNSUPPORTED;
     if (batch > 65535 || num_q_heads > 65535) return KV_ERR_UNSUPPORTED;
     if ((int64_t)max_q_len > (int64_t)65535 * 16 * kPrefillQueryBlocks) return KV_ERR_UNSUPPORTED;
-    if (batch == 0 || max_q_len == 0) return KV_OK;
+    if (total_q < 0 || key_splits < 0 || key_splits > kPrefillMaxKeySplits) return KV_ERR_SHAPE;
+    if (batch == 0 || max_q_len == 0 || total_q == 0) return KV_OK;
     if (!out || !q || !block_table || !context_lens || !q_starts) return KV_ERR_NULL;
     if (!aligned16(out) || !aligned16(q)) return KV_ERR_ALIGN;
+    if (key_splits == 0) key_splits = 1;
+    if (key_splits > 1) {
+        if (!workspace || workspace_bytes < kv_prefill_workspace_bytes(total_q, num_q_heads, pool->head_dim, key_splits))
+            return KV_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return KV_ERR_ALIGN;
+    }
     const int32_t group = num_q_heads / pool->num_kv_heads;
     PrefillParams p;
+    p.key_splits = key_splits;
+    p.total_q = total_q;
+    p.ws = (float*)workspace;
     p.out = out;
     p.q = (const uint16_t*)q;
     p.pool = pool->base;

@@ -64,7 +64,11 @@ struct PrefillParams {
     int32_t kv_fp8;
     float scale_log2e;         // scale * log2(e), times the K scale of an FP8 pool; > 0
     float out_scale;           // 1, or the V scale of an FP8 pool
+    int32_t key_splits;        // >= 1 parts of the key range, each handled by its own workgroups
+    int64_t total_q;           // packed query rows (only used when key_splits > 1)
+    float* ws;                 // [key_splits][total_q][Hq][D + kRecordPad] fp32 (only when key_splits > 1)
 };
+constexpr int kPrefillMaxKeySplits = 16;
 
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int max_q_len, hipStream_t stream);
 

@@ -27,6 +27,12 @@
 
 namespace kvflow {
 
+// Floats per record of a part of the key range: O[head_dim], running max, denominator, pad to 16 bytes.
+template <int D>
+constexpr int kPrefillRecord = D + kRecordPad;
+// "No key seen yet": a finite stand-in for minus infinity, so that differences of maxima stay finite.
+constexpr float kPrefillNoMax = -1e30f;
+
 template <int D>
 struct PrefillShape {
     static constexpr int kSteps = D / 32;                 // MFMA k-steps over the head dimension
@@ -67,7 +73,9 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     const int n = qs_ptr[b + 1] - qs;
     const int hpw = p.heads_per_wg, tbw = kPrefillWaves / hpw;
     const int ntb = (n + QW - 1) / QW;                    // token ranges of this sequence
-    const int tbg = (ntb + tbw - 1) / tbw - 1 - (int)blockIdx.y;
+    // blockIdx.y = (group of token ranges, heaviest first) x (part of the key range)
+    const int ns = p.key_splits, split = (int)blockIdx.y % ns;
+    const int tbg = (ntb + tbw - 1) / tbw - 1 - (int)blockIdx.y / ns;
     if (tbg < 0) return;
 
     const int head = blockIdx.x * hpw + wave % hpw;
@@ -107,6 +115,24 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         }
     };
 
+    // With the key range cut into parts, a part leaves one record per (query row, head): O un-normalised,
+    // running max, denominator; a second kernel combines the parts of a row in ascending order.
+    auto store_records = [&](const f32x4 (&o)[NQB][S::kDTiles], const float (&m)[NQB], const float (&l)[NQB]) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+            if (qidx[qb] >= n) continue;
+            const bool none = qpos[qb] < 0;                          // a query before position 0 sees nothing
+            float* rec = p.ws + (((int64_t)split * p.total_q + qs + qidx[qb]) * p.num_q_heads + head) * kPrefillRecord<D>;
+#pragma unroll
+            for (int dt = 0; dt < S::kDTiles; ++dt)
+                *(f32x4*)(rec + 16 * dt + 4 * g) = none ? f32x4{0.f, 0.f, 0.f, 0.f} : o[qb][dt];
+            if (g == 0) {
+                rec[D] = none ? kPrefillNoMax : m[qb];
+                rec[D + 1] = none ? 0.f : l[qb];
+            }
+        }
+    };
+
     f32x4 oacc[NQB][S::kDTiles];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb)
@@ -116,17 +142,26 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     if (L <= 0) {                                         // no cached token at all: rows of zeros
         if (active) {
             const float z[NQB] = {};
-            store_rows(oacc, z);
+            if (ns == 1) {
+                store_rows(oacc, z);
+            } else {
+                float none[NQB];
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb) none[qb] = kPrefillNoMax;
+                store_records(oacc, none, z);
+            }
         }
         return;
     }
 
     // keys this workgroup walks: up to the position of its last query
     const int jl = min((tbg * tbw + tbw) * QW, n) - 1;
-    const int nt = (max(p0 + jl, 0) >> 5) + 1;
-    // this wavefront: first query position (tiles that reach past it need the mask), last tile
+    const int nt_all = (max(p0 + jl, 0) >> 5) + 1;
+    // this workgroup's part of them: tiles [t0, nt)
+    const int t0 = (int)((int64_t)split * nt_all / ns), nt = (int)((int64_t)(split + 1) * nt_all / ns);
+    // this wavefront: first query position (tiles that reach past it need the mask), last tile (in this part)
     const int pa = p0 + j0;
-    const int tl = active ? (max(p0 + min(j0 + QW, n) - 1, 0) >> 5) : -1;
+    const int tl = active ? min(max(p0 + min(j0 + QW, n) - 1, 0) >> 5, nt - 1) : t0 - 1;
 
     // ---- global -> LDS staging of K/V tiles
     const int bs = p.block_size;
@@ -211,7 +246,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     float m_run[NQB];
     f32x4 l_acc[NQB];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_acc[qb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = kPrefillNoMax; l_acc[qb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
     const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
 
     const int k_off = j * S::kKPitch + 16 * g;            // K operand: row j, channels 8g ..
@@ -268,7 +303,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                 float v = fmaxf(mx[qb], __shfl_xor(mx[qb], 16));
                 v = fmaxf(v, __shfl_xor(v, 32));
                 const float m_new = fmaxf(m_run[qb], v);
-                // tile 0 holds key 0, visible to every query, so m_new is finite from the first tile on
+                // m_run starts at a huge negative finite number, so nothing here is inf - inf
                 const float alpha = fast_exp2(m_run[qb] - m_new);
                 m_run[qb] = m_new;
                 l_acc[qb] *= alpha;
@@ -318,18 +353,18 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     unsigned char* ring[S::kRing];                        // ring[i] holds tile t + i
 #pragma unroll
     for (int i = 0; i < S::kRing; ++i) ring[i] = smem + i * S::kStage;
-    int id = load_id(0);
-    gload(0, id);
-    id = load_id(1);
-    lstore(0, ring[0]);
-    gload(1, id);
-    id = load_id(2);
-    lstore(1, ring[1]);
-    gload(2, id);
-    id = load_id(3);
-    lstore(2, ring[2]);
-    gload(3, id);
-    id = load_id(4);
+    int id = load_id(t0);
+    gload(t0, id);
+    id = load_id(t0 + 1);
+    lstore(t0, ring[0]);
+    gload(t0 + 1, id);
+    id = load_id(t0 + 2);
+    lstore(t0 + 1, ring[1]);
+    gload(t0 + 2, id);
+    id = load_id(t0 + 3);
+    lstore(t0 + 2, ring[2]);
+    gload(t0 + 3, id);
+    id = load_id(t0 + 4);
     __syncthreads();
     auto stage = [&](int t) {                             // part of step t
         lstore(t + 3, ring[3]);
@@ -343,10 +378,10 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         ring[S::kRing - 1] = old;
     };
     f32x4 sa[NQB][2], sb[NQB][2];
-    if (tl >= 0) {
+    if (tl >= t0) {
         read_k(ring[0]);
         qk(sa);
-        settle(0, sa);
+        settle(t0, sa);
         read_k(ring[1]);
     }
     // a step whose tile has a successor for this wavefront
@@ -362,7 +397,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         rotate();
         __syncthreads();
     };
-    int t = 0;
+    int t = t0;
     for (; t + 1 < tl; t += 2) {
         step(t, sa, sb);
         step(t + 1, sb, sa);
@@ -390,10 +425,47 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     }
 
     if (active) {
-        float inv[NQB];
+        float inv[NQB], l[NQB];
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) inv[qb] = 1.f / l_acc[qb][0];
-        store_rows(oacc, inv);
+        for (int qb = 0; qb < NQB; ++qb) { l[qb] = l_acc[qb][0]; inv[qb] = 1.f / l[qb]; }
+        if (ns == 1) store_rows(oacc, inv);
+        else store_records(oacc, m_run, l);
+    }
+}
+
+// Combines the records that the parts of the key range left for one (query row, head), in ascending
+// order of the parts, and normalises.  A lane owns 4 channels of a row.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_merge_kernel(const PrefillParams p)
+{
+    constexpr int kLanes = D / 4, kRows = 256 / kLanes, kRec = kPrefillRecord<D>;
+    const int64_t rows = p.total_q * p.num_q_heads;
+    const int64_t row = (int64_t)blockIdx.x * kRows + threadIdx.x / kLanes;
+    const int c = threadIdx.x % kLanes;
+    if (row >= rows) return;
+    const int ns = p.key_splits;
+    const int64_t stride = rows * kRec;                   // part s -> part s + 1, same row
+    const float* rec = p.ws + row * kRec;
+    float M = kPrefillNoMax;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, rec[s * stride + D]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        const float w = fast_exp2(rec[s * stride + D] - M);
+        acc += w * *(const f32x4*)(rec + s * stride + 4 * c);
+        l += w * rec[s * stride + D + 1];
+    }
+    // no visible key in any part (a query before position 0, an empty context): a row of zeros
+    const float f = l > 0.f ? p.out_scale / l : 0.f;
+    acc *= f;
+    if (p.out_f32) {
+        *(f32x4*)((float*)p.out + row * D + 4 * c) = acc;
+    } else {
+        typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+        bf16x4 h;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) h[i] = (__bf16)acc[i];
+        *(bf16x4*)((__bf16*)p.out + row * D + 4 * c) = h;
     }
 }
 
@@ -403,9 +475,9 @@ static hipError_t launch_prefill_d(const PrefillParams& p, int max_q_len, hipStr
     constexpr int NQB = kPrefillQueryBlocks;
     const int tbw = kPrefillWaves / p.heads_per_wg;
     const int ranges = (max_q_len + 16 * NQB - 1) / (16 * NQB);
-    const dim3 grid((uint32_t)(p.num_q_heads / p.heads_per_wg), (uint32_t)((ranges + tbw - 1) / tbw),
-                    (uint32_t)p.batch);
-    if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
+    const int64_t gy = (int64_t)((ranges + tbw - 1) / tbw) * p.key_splits;
+    if (gy > 65535 || p.batch > 65535) return hipErrorInvalidValue;
+    const dim3 grid((uint32_t)(p.num_q_heads / p.heads_per_wg), (uint32_t)gy, (uint32_t)p.batch);
     using S = PrefillShape<D>;
     // the ring is larger than the 64 KiB a kernel gets without asking
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<D, NQB, FP8>),
@@ -413,6 +485,12 @@ static hipError_t launch_prefill_d(const PrefillParams& p, int max_q_len, hipStr
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((prefill_kernel<D, NQB, FP8>), grid, dim3(kPrefillThreads), S::kLdsBytes, stream, p, p.q,
                        p.pool, p.block_table, p.context_lens, p.q_starts, p.out);
+    e = hipGetLastError();
+    if (e != hipSuccess || p.key_splits == 1) return e;
+    constexpr int kRows = 256 / (D / 4);
+    const int64_t rows = p.total_q * p.num_q_heads;
+    if ((rows + kRows - 1) / kRows > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(prefill_merge_kernel<D>, dim3((uint32_t)((rows + kRows - 1) / kRows)), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 

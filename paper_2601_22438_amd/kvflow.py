@@ -55,7 +55,11 @@ def load() -> ctypes.CDLL:
     lib.kv_decode_attn.restype = ctypes.c_int
     lib.kv_decode_attn.argtypes = [P, I32, P, PD, P, I32, P, I32, I32, I32, F, I32, P, SZ, P]
     lib.kv_prefill_attn.restype = ctypes.c_int
-    lib.kv_prefill_attn.argtypes = [P, I32, P, PD, P, I32, P, P, I32, I32, I32, F, P]
+    lib.kv_prefill_attn.argtypes = [P, I32, P, PD, P, I32, P, P, I32, I32, I32, I64, F, I32, P, SZ, P]
+    lib.kv_prefill_key_splits.restype = I32
+    lib.kv_prefill_key_splits.argtypes = [I32, I32, I32, I32, I32]
+    lib.kv_prefill_workspace_bytes.restype = SZ
+    lib.kv_prefill_workspace_bytes.argtypes = [I64, I32, I32, I32]
     lib.kv_pack_blocks.restype = ctypes.c_int
     lib.kv_pack_blocks.argtypes = [P, PD, P, I64, P]
     lib.kv_restore_blocks.restype = ctypes.c_int
@@ -148,15 +152,26 @@ def kv_decode_attn(out, q, pool, block_table, context_lens, max_context_len, sca
         float(scale), int(num_workgroups), _ptr(workspace), ws_bytes, _stream_handle(stream)))
 
 
-def kv_prefill_attn(out, q, pool, block_table, context_lens, q_starts, max_q_len, scale, stream=None) -> None:
+def kv_prefill_key_splits(batch, num_q_heads, num_kv_heads, max_q_len, max_context_len) -> int:
+    return int(load().kv_prefill_key_splits(batch, num_q_heads, num_kv_heads, max_q_len, max_context_len))
+
+
+def kv_prefill_workspace_bytes(total_q, num_q_heads, head_dim, key_splits) -> int:
+    return int(load().kv_prefill_workspace_bytes(total_q, num_q_heads, head_dim, key_splits))
+
+
+def kv_prefill_attn(out, q, pool, block_table, context_lens, q_starts, max_q_len, scale, key_splits=1,
+                    workspace=None, stream=None) -> None:
     """Enqueue causal attention of the packed query tokens ``q`` ([T][Hq][D]) over the pool; ``out`` is
-    written in place ([T][Hq][D], bf16 or fp32)."""
-    _, num_q_heads, _ = q.shape
+    written in place ([T][Hq][D], bf16 or fp32).  ``workspace`` is needed for key_splits > 1."""
+    total_q, num_q_heads, _ = q.shape
     out_dtype = {torch.bfloat16: KV_DTYPE_BF16, torch.float32: KV_DTYPE_F32}[out.dtype]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().kv_prefill_attn(
         _ptr(out), out_dtype, _ptr(q), ctypes.byref(pool_desc(pool)), _ptr(block_table),
         block_table.shape[1], _ptr(context_lens), _ptr(q_starts), context_lens.numel(), num_q_heads,
-        int(max_q_len), float(scale), _stream_handle(stream)))
+        int(max_q_len), int(total_q), float(scale), int(key_splits), _ptr(workspace), ws_bytes,
+        _stream_handle(stream)))
 
 
 def kv_pack_blocks(replica, pool, block_ids, n=None, stream=None) -> None:

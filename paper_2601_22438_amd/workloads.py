@@ -434,3 +434,11 @@ def chunked_recompute(seed=7, shrink=1, batch=8, chunk=2048) -> PrefillCase:
     q_lens = np.minimum(lens, max(1, chunk // shrink)).astype(np.int32)
     return make_prefill_case("chunked_recompute", seed, g, lens, q_lens, max_blocks_per_seq=4096 // shrink,
                              dirty="last")
+
+
+def short_chunk_recompute(seed=8) -> PrefillCase:
+    """One request whose newest 256 tokens are recomputed over a 40 000-token restored prefix: few query
+    tokens, so the work only fills the chip when the key range is cut into parts."""
+    g = Geometry(32, 8, 128, 16)
+    return make_prefill_case("short_chunk_recompute", seed, g, np.array([40_000], np.int32),
+                             np.array([256], np.int32), max_blocks_per_seq=2500, dirty="last")

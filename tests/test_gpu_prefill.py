@@ -23,14 +23,20 @@ class DevicePrefill:
         self.context_lens = torch.from_numpy(kv.context_lens).cuda()
         self.q_starts = torch.from_numpy(case.q_starts).cuda()
 
-    def run(self, out_dtype=torch.float32, canary_rows=3, max_q_len=None, block_table=None, pool=None):
+    def run(self, out_dtype=torch.float32, canary_rows=3, max_q_len=None, block_table=None, pool=None,
+            key_splits=1):
         c, g = self.case, self.case.geom
         # rows after the last packed query token must stay untouched
         out = torch.full((c.total_q + canary_rows, g.num_q_heads, g.head_dim), float("nan"),
                          dtype=out_dtype, device="cuda")
-        kvflow.kv_prefill_attn(out, self.q, self.pool if pool is None else pool,
+        ws = None
+        if key_splits > 1:                                  # workspace contents on entry must not matter
+            nbytes = kvflow.kv_prefill_workspace_bytes(c.total_q, g.num_q_heads, g.head_dim, key_splits)
+            ws = torch.full((max(nbytes, 4) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        kvflow.kv_prefill_attn(out[:c.total_q], self.q, self.pool if pool is None else pool,
                                self.block_table if block_table is None else block_table, self.context_lens,
-                               self.q_starts, c.max_q_len if max_q_len is None else max_q_len, float(g.scale))
+                               self.q_starts, c.max_q_len if max_q_len is None else max_q_len, float(g.scale),
+                               key_splits, ws)
         torch.cuda.synchronize()
         assert torch.isnan(out[c.total_q:].float()).all(), "wrote past the last query row"
         return out[:c.total_q]
@@ -207,3 +213,59 @@ def test_fp8_recompute_shrunk_sampled_rows(oracle):
     got = DevicePrefill(case, k_scale=W.FP8_KV_SCALE, v_scale=W.FP8_KV_SCALE).run(canary_rows=1)
     pick = got[torch.from_numpy(rows[:, 0].astype(np.int64)).cuda(), torch.from_numpy(rows[:, 1].astype(np.int64)).cuda()]
     U.assert_close_to_oracle(pick, want, "fp8 recompute/4")
+
+
+# ---- key range cut into parts (few query tokens over long contexts)
+@pytest.mark.parametrize("key_splits", [2, 3, 16])
+def test_key_splits_match_oracle_on_ragged_cases(oracle, key_splits):
+    """More parts than tiles, parts that end on the diagonal, sequences without queries or without context."""
+    case = W.prefill_tiny(seed=70)
+    want = oracle_out(oracle, case)
+    dev = DevicePrefill(case)
+    U.assert_close_to_oracle(dev.run(key_splits=key_splits), want, f"tiny, {key_splits} parts")
+    got16 = dev.run(torch.bfloat16, key_splits=key_splits)
+    assert np.abs(got16.double().cpu().numpy() - want).max() <= U.MAX_ABS + 2.0 ** -8 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("geom", [(4, 4, 128, 16), (6, 2, 64, 16), (16, 2, 128, 32)])
+def test_key_splits_geometries(oracle, geom):
+    Hq, Hkv, D, bs = geom
+    g = W.Geometry(Hq, Hkv, D, bs)
+    lens = np.array([1, 33, 700, 300, 1000], np.int32)
+    q_lens = np.array([1, 33, 40, 300, 7], np.int32)
+    case = W.make_prefill_case("splitgeom", 71 + Hq, g, lens, q_lens, max_blocks_per_seq=-(-1000 // bs), dirty="last")
+    U.assert_close_to_oracle(DevicePrefill(case).run(key_splits=5), oracle_out(oracle, case), str(geom))
+
+
+def test_key_splits_excess_queries_and_empty_context(oracle):
+    g = W.Geometry(8, 2, 64, 16)
+    case = W.make_prefill_case("excess_split", 72, g, np.array([70, 20], np.int32), np.array([70, 20], np.int32),
+                               max_blocks_per_seq=8, dirty="last")
+    case.kv.context_lens[:] = [0, 12]
+    U.assert_close_to_oracle(DevicePrefill(case).run(key_splits=4), oracle_out(oracle, case), "excess, 4 parts")
+
+
+def test_key_splits_fp8_pool(oracle):
+    g = W.Geometry(8, 2, 128, 16, kv_elt_bytes=1)
+    case = W.make_prefill_case("fp8split", 73, g, np.array([900, 260], np.int32), np.array([33, 260], np.int32),
+                               max_blocks_per_seq=64, dirty="last")
+    kv = case.kv
+    want = oracle.prefill_attn(case.q, kv.pool, kv.block_table, kv.context_lens, case.q_starts, g.scale,
+                               k_scale=0.25, v_scale=0.5)
+    U.assert_close_to_oracle(DevicePrefill(case, k_scale=0.25, v_scale=0.5).run(key_splits=6), want, "fp8, 6 parts")
+
+
+def test_short_chunk_over_long_context_with_suggested_splits(oracle):
+    """One sequence, 256 newest tokens over 40k cached ones: the library suggests cutting the key range."""
+    g = W.Geometry(32, 8, 128, 16)
+    lens = np.array([40_000], np.int32)
+    case = W.make_prefill_case("short_chunk", 74, g, lens, np.array([256], np.int32), max_blocks_per_seq=2500,
+                               dirty="last")
+    ks = kvflow.kv_prefill_key_splits(1, 32, 8, 256, 40_000)
+    assert ks == 16
+    rows = sample_rows(case, 150, 75)
+    want = oracle_out(oracle, case, rows=rows)
+    dev = DevicePrefill(case)
+    idx = (torch.from_numpy(rows[:, 0].astype(np.int64)).cuda(), torch.from_numpy(rows[:, 1].astype(np.int64)).cuda())
+    U.assert_close_to_oracle(dev.run(key_splits=ks)[idx], want, "16 parts")
+    U.assert_close_to_oracle(dev.run(key_splits=1)[idx], want, "1 part")

@@ -160,15 +160,35 @@ def test_fp8_pool_descriptor_checks(lib):
 def test_prefill_rejects_bad_arguments_before_any_launch(lib):
     from paper_2601_22438_amd import kvflow
     ok = desc(kvflow)
-    pf = lambda p=ok, out=0x20000, q=0x30000, tb=0x40000, mb=4, lens=0x50000, qs=0x60000, b=2, hq=8, mq=64, od=1: \
-        lib.kv_prefill_attn(out, od, q, ctypes.byref(p), tb, mb, lens, qs, b, hq, mq, 0.125, None)
-    assert pf(b=0) == 0 and pf(mq=0) == 0                                         # nothing to do
+
+    def pf(p=ok, out=0x20000, q=0x30000, tb=0x40000, mb=4, lens=0x50000, qs=0x60000, b=2, hq=8, mq=64, od=1,
+           tq=100, scale=0.125, ks=1, ws=0, wsb=0):
+        return lib.kv_prefill_attn(out, od, q, ctypes.byref(p), tb, mb, lens, qs, b, hq, mq, tq, scale, ks, ws, wsb,
+                                   None)
+    assert pf(b=0) == 0 and pf(mq=0) == 0 and pf(tq=0) == 0                       # nothing to do
     assert pf(out=0) == -1 and pf(q=0) == -1 and pf(tb=0) == -1 and pf(lens=0) == -1 and pf(qs=0) == -1
     assert pf(p=desc(kvflow, base=0)) == -1
-    assert pf(b=-1) == -2 and pf(mq=-1) == -2 and pf(mb=0) == -2 and pf(hq=7) == -2
+    assert pf(b=-1) == -2 and pf(mq=-1) == -2 and pf(mb=0) == -2 and pf(hq=7) == -2 and pf(tq=-1) == -2
+    assert pf(ks=-1) == -2 and pf(ks=17) == -2
     assert pf(p=desc(kvflow, d=96)) == -3 and pf(od=2) == -3 and pf(b=65536) == -3
     assert pf(p=kvflow.kv_pool_desc(0x10000, 8, 2, 16, 64, 2, 0.0, 0.25)) == -2   # FP8 pool with a bad scale
-    sc = lambda v: lib.kv_prefill_attn(0x20000, 1, 0x30000, ctypes.byref(ok), 0x40000, 4, 0x50000, 0x60000, 2, 8, 64,
-                                       v, None)
-    assert sc(0.0) == -2 and sc(-0.125) == -2 and sc(float("inf")) == -2 and sc(float("nan")) == -2
     assert pf(out=0x20008) == -4 and pf(q=0x30004) == -4
+    for bad in (0.0, -0.125, float("inf"), float("nan")):
+        assert pf(scale=bad) == -2
+    # a split key range needs its workspace
+    need = kvflow.kv_prefill_workspace_bytes(100, 8, 64, 4)
+    assert need == 4 * 100 * 8 * (64 + 4) * 4
+    assert pf(ks=4) == -5 and pf(ks=4, ws=0x70000, wsb=need - 1) == -5 and pf(ks=4, ws=0x70004, wsb=need) == -4
+    assert kvflow.kv_prefill_workspace_bytes(100, 8, 64, 1) == 0 and kvflow.kv_prefill_workspace_bytes(100, 8, 64, 17) == 0
+
+
+def test_prefill_key_split_suggestion():
+    from paper_2601_22438_amd import kvflow
+    # many query tokens: the token ranges fill the chip by themselves
+    assert kvflow.kv_prefill_key_splits(8, 32, 8, 8192, 8192) == 1
+    # one sequence, a 256-token chunk over 64k tokens: 8 head groups x 4 range pairs = 32 workgroups -> 16 parts
+    assert kvflow.kv_prefill_key_splits(1, 32, 8, 256, 65536) == 16
+    # short contexts are not cut below 16 tiles per part
+    assert kvflow.kv_prefill_key_splits(1, 32, 8, 256, 1024) == 2
+    assert kvflow.kv_prefill_key_splits(1, 32, 8, 64, 300) == 1
+    assert kvflow.kv_prefill_key_splits(0, 32, 8, 256, 1024) == 0 and kvflow.kv_prefill_key_splits(1, 33, 8, 256, 1024) == 0
