@@ -30,8 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core peak
 # HBM traffic per decode launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
 # WRITE_SIZE), scaled by the same counters on a plain copy of known size; see profiles/.  Valid
 # only for the kernel sources (kv_decode.hip + kv_decode_common.h) the counters were taken with.
-DECODE_TRAFFIC = {"kernel_sha256": "5f5326fb0d0c0284415bd4c147c147866523efe278b26ee5c63f3a3f5be681d2",
-                  "fetch_bytes": 1329065086, "write_bytes": 4525947}
+DECODE_TRAFFIC = {"kernel_sha256": "2f1735a2bd070ae0452f2b9d8d173d1adf09ac46fcd97d74fbe7e45d24f5c7c8",
+                  "fetch_bytes": 1329364413, "write_bytes": 4525801}
 
 PAPER_CONTEXT = {
     "note": "end-to-end serving figures from the paper, other hardware, context only",
@@ -481,8 +481,9 @@ def main():
     g = case.geom
     d = main_res["decode"]
     achieved = main_res["decode_GBps"]
-    src = b"".join(open(os.path.join(ROOT, "paper_2601_22438_amd", "csrc", f), "rb").read()
-                   for f in ("kv_decode.hip", "kv_decode_common.h"))
+    # everything the decode kernels are built from: their sources, the shared constants, the compile flags
+    src = b"".join(open(os.path.join(ROOT, "paper_2601_22438_amd", f), "rb").read()
+                   for f in ("csrc/kv_decode.hip", "csrc/kv_decode_common.h", "csrc/kv_internal.h", "build.py"))
     traffic = None
     if DECODE_TRAFFIC["kernel_sha256"] == hashlib.sha256(src).hexdigest():
         traffic = DECODE_TRAFFIC["fetch_bytes"] + DECODE_TRAFFIC["write_bytes"]

@@ -15,6 +15,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept off for the device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # device code only: no operation here has a NaN operand by design (masked scores are -inf, rows
+    # that must not count are zeroed or selected away), so maxima need not quiet signalling NaNs first
+    "-Xarch_device", "-fno-honor-nans",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 
