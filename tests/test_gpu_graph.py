@@ -62,3 +62,42 @@ def test_step_captured_in_a_graph_replays_like_eager(oracle):
             eager_out = out.clone()
             assert_close_to_oracle(eager_out, oracle.decode_attn(q2, case.pool, case.block_table, case.context_lens,
                                                                  g.scale), "replay with new q")
+
+
+@pytest.mark.parametrize("key_splits", [1, 3])
+def test_recompute_call_captured_in_a_graph(oracle, key_splits):
+    """kv_prefill_attn (with and without a cut key range) replays like eager, also when the first call of
+    the process for this kernel happens during capture."""
+    g = W.Geometry(8, 2, 64 if key_splits == 1 else 128, 16)
+    case = W.make_prefill_case("graph_prefill", 910 + key_splits, g, np.array([300, 77], np.int32),
+                               np.array([120, 77], np.int32), max_blocks_per_seq=32, dirty="last")
+    kv = case.kv
+    q, pool = bf16_tensor(case.q), bf16_tensor(kv.pool)
+    table, lens = torch.from_numpy(kv.block_table).cuda(), torch.from_numpy(kv.context_lens).cuda()
+    starts = torch.from_numpy(case.q_starts).cuda()
+    out = torch.zeros((case.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
+    nbytes = kvflow.kv_prefill_workspace_bytes(case.total_q, g.num_q_heads, g.head_dim, key_splits)
+    ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device="cuda")
+    want = oracle.prefill_attn(case.q, kv.pool, kv.block_table, kv.context_lens, case.q_starts, g.scale)
+
+    def call():
+        kvflow.kv_prefill_attn(out, q, pool, table, lens, starts, case.max_q_len, float(g.scale), key_splits, ws)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.synchronize()
+    for i in range(3):
+        out.zero_(); ws.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_close_to_oracle(out, want, f"replay {i}")
+    replayed = out.clone()
+    out.zero_()
+    call()
+    torch.cuda.synchronize()
+    assert torch.equal(out, replayed)
