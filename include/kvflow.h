@@ -267,6 +267,12 @@ int kv_validate_decode(const kv_pool_desc* pool, const int32_t* block_table,
                        int32_t max_context_len, void* stream);
 int kv_validate_block_ids(const kv_pool_desc* pool, const int32_t* block_ids, int64_t n,
                           int32_t require_distinct, void* stream);
+/* Preconditions of kv_prefill_attn: q_starts starts at 0, does not decrease, ends at total_q; every
+ * sequence has 0 <= n <= max_q_len query tokens and at least n cached ones; lengths and table entries
+ * as for kv_validate_decode. */
+int kv_validate_prefill(const kv_pool_desc* pool, const int32_t* block_table, int32_t max_blocks_per_seq,
+                        const int32_t* context_lens, const int32_t* q_starts, int32_t batch,
+                        int32_t max_q_len, int64_t total_q, void* stream);
 
 /* Static, human-readable text for a kv_status value. */
 const char* kv_status_string(int status);

@@ -336,6 +336,33 @@ int kv_validate_decode(const kv_pool_desc* pool, const int32_t* block_table, int
     return KV_OK;
 }
 
+int kv_validate_prefill(const kv_pool_desc* pool, const int32_t* block_table, int32_t max_blocks_per_seq,
+                        const int32_t* context_lens, const int32_t* q_starts, int32_t batch, int32_t max_q_len,
+                        int64_t total_q, void* stream)
+{
+    int rc = check_pool(pool);
+    if (rc != KV_OK) return rc;
+    if (batch < 0 || max_blocks_per_seq <= 0 || max_q_len < 0 || total_q < 0) return KV_ERR_SHAPE;
+    if (batch == 0) return total_q == 0 ? KV_OK : KV_ERR_SHAPE;
+    if (!block_table || !context_lens || !q_starts) return KV_ERR_NULL;
+    std::vector<int32_t> lens((size_t)batch), starts((size_t)batch + 1);
+    hipStream_t s = (hipStream_t)stream;
+    if (hipMemcpyAsync(lens.data(), context_lens, lens.size() * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipMemcpyAsync(starts.data(), q_starts, starts.size() * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return KV_ERR_LAUNCH;
+    if (starts[0] != 0 || starts[(size_t)batch] != total_q) return KV_ERR_CONTENT;
+    int32_t max_len = 0;
+    for (int32_t b = 0; b < batch; ++b) {
+        const int64_t n = (int64_t)starts[(size_t)b + 1] - starts[(size_t)b];
+        // more query tokens than cached tokens is outside the contract of a recomputation
+        if (n < 0 || n > max_q_len || lens[(size_t)b] < 0 || n > lens[(size_t)b]) return KV_ERR_CONTENT;
+        if (lens[(size_t)b] > max_len) max_len = lens[(size_t)b];
+    }
+    // table entries and lengths against the table row: the decode check, with the largest length as bound
+    return kv_validate_decode(pool, block_table, max_blocks_per_seq, context_lens, batch, max_len, stream);
+}
+
 int kv_validate_block_ids(const kv_pool_desc* pool, const int32_t* block_ids, int64_t n,
                           int32_t require_distinct, void* stream)
 {

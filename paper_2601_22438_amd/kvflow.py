@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
     lib.kv_collect_dirty.argtypes = [P, I64, P, I64, P, I32, P]
     lib.kv_validate_decode.restype = ctypes.c_int
     lib.kv_validate_decode.argtypes = [PD, P, I32, P, I32, I32, P]
+    lib.kv_validate_prefill.restype = ctypes.c_int
+    lib.kv_validate_prefill.argtypes = [PD, P, I32, P, P, I32, I32, I64, P]
     lib.kv_validate_block_ids.restype = ctypes.c_int
     lib.kv_validate_block_ids.argtypes = [PD, P, I64, I32, P]
     lib.kv_status_string.restype, lib.kv_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
@@ -218,6 +220,12 @@ def kv_validate_decode(pool, block_table, context_lens, max_context_len, stream=
     return int(load().kv_validate_decode(
         ctypes.byref(pool_desc(pool)), _ptr(block_table), block_table.shape[1], _ptr(context_lens),
         context_lens.numel(), int(max_context_len), _stream_handle(stream)))
+
+
+def kv_validate_prefill(pool, block_table, context_lens, q_starts, max_q_len, total_q, stream=None) -> int:
+    return int(load().kv_validate_prefill(
+        ctypes.byref(pool_desc(pool)), _ptr(block_table), block_table.shape[1], _ptr(context_lens), _ptr(q_starts),
+        context_lens.numel(), int(max_q_len), int(total_q), _stream_handle(stream)))
 
 
 def kv_validate_block_ids(pool, block_ids, require_distinct=False, stream=None) -> int:

@@ -269,3 +269,22 @@ def test_short_chunk_over_long_context_with_suggested_splits(oracle):
     idx = (torch.from_numpy(rows[:, 0].astype(np.int64)).cuda(), torch.from_numpy(rows[:, 1].astype(np.int64)).cuda())
     U.assert_close_to_oracle(dev.run(key_splits=ks)[idx], want, "16 parts")
     U.assert_close_to_oracle(dev.run(key_splits=1)[idx], want, "1 part")
+
+
+def test_validate_prefill_catches_bad_device_contents():
+    case = W.prefill_tiny(seed=90)
+    dev = DevicePrefill(case)
+    args = lambda **kw: (kw.get("pool", dev.pool), kw.get("table", dev.block_table), kw.get("lens", dev.context_lens),
+                         kw.get("starts", dev.q_starts), kw.get("max_q", case.max_q_len), kw.get("total", case.total_q))
+    assert kvflow.kv_validate_prefill(*args()) == 0
+    assert kvflow.kv_validate_prefill(*args(max_q=case.max_q_len - 1)) == -7
+    assert kvflow.kv_validate_prefill(*args(total=case.total_q + 1)) == -7
+    short = dev.context_lens.clone()
+    short[0] = int(case.q_lens[0]) - 1                               # more queries than cached tokens
+    assert kvflow.kv_validate_prefill(*args(lens=short)) == -7
+    bad = dev.block_table.clone()
+    bad[1, 0] = case.kv.num_blocks
+    assert kvflow.kv_validate_prefill(*args(table=bad)) == -7
+    dec = dev.q_starts.clone()
+    dec[2] = dec[1] - 1
+    assert kvflow.kv_validate_prefill(*args(starts=dec)) == -7
