@@ -20,8 +20,10 @@
 // fragments of tile t + 2 and the V fragments of tile t are read from LDS a phase before use.
 //
 // Grid: x = query-head group (fastest, so that with 8 or more groups the workgroups that read
-// one KV head's tiles land on one XCD and share its L2), y = token range, heaviest (latest)
-// first, z = sequence.
+// one KV head's tiles land on one XCD and share its L2), y = (token range, heaviest (latest)
+// first) x (part of the key range), z = sequence.  With more than one part per key range every
+// workgroup leaves a record per (query row, head) and prefill_merge_kernel combines them; this
+// fills the chip when there are few query tokens over long contexts.
 
 #include "kv_decode_common.h"
 
