@@ -448,14 +448,30 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(const PrefillParams 
     const int ns = p.key_splits;
     const int64_t stride = rows * kRec;                   // part s -> part s + 1, same row
     const float* rec = p.ws + row * kRec;
+    // every load is issued before the first use: the kernel is a handful of cold reads per row
+    float m[kPrefillMaxKeySplits], l_part[kPrefillMaxKeySplits];
+    f32x4 o[kPrefillMaxKeySplits];
+#pragma unroll
+    for (int s = 0; s < kPrefillMaxKeySplits; ++s) {
+        m[s] = kPrefillNoMax;
+        l_part[s] = 0.f;
+        o[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (s < ns) {
+            m[s] = rec[s * stride + D];
+            l_part[s] = rec[s * stride + D + 1];
+            o[s] = *(const f32x4*)(rec + s * stride + 4 * c);
+        }
+    }
     float M = kPrefillNoMax;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, rec[s * stride + D]);
+#pragma unroll
+    for (int s = 0; s < kPrefillMaxKeySplits; ++s) M = fmaxf(M, m[s]);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float l = 0.f;
-    for (int s = 0; s < ns; ++s) {
-        const float w = fast_exp2(rec[s * stride + D] - M);
-        acc += w * *(const f32x4*)(rec + s * stride + 4 * c);
-        l += w * rec[s * stride + D + 1];
+#pragma unroll
+    for (int s = 0; s < kPrefillMaxKeySplits; ++s) {       // absent parts: weight of a zero record
+        const float w = fast_exp2(m[s] - M);
+        acc += w * o[s];
+        l += w * l_part[s];
     }
     // no visible key in any part (a query before position 0, an empty context): a row of zeros
     const float f = l > 0.f ? p.out_scale / l : 0.f;
