@@ -5,6 +5,7 @@ this package; the product package never does.
 """
 from .kv_oracle import (  # noqa: F401
     OracleError,
+    append_packed,
     append_tokens,
     bitmap_words,
     build,

@@ -370,3 +370,40 @@ int kvo_prefill_attn(double* out, const uint16_t* q, const void* pool, int kv_fp
     }
     return used;
 }
+
+/*
+ * Writing the K/V rows of recomputed (or prefilled) tokens into the pool: the step before
+ * kvo_prefill_attn, with the same conventions.  k_new, v_new: [total_q][num_kv_heads][head_dim]
+ * 16-bit elements, sequences packed in batch order; token i of sequence b (packed row
+ * q_starts[b] + i) goes to position context_lens[b] - q_len_b + i of that sequence, and the block
+ * that holds it is marked dirty.  Rows whose position would be negative are skipped.
+ */
+int kvo_append_packed(uint16_t* pool, int64_t num_blocks, int num_kv_heads, int block_size, int head_dim,
+                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
+                      int max_blocks_per_seq, const int32_t* context_lens, const int32_t* q_starts, int batch,
+                      uint32_t* dirty_bitmap)
+{
+    int rc = check_decode_args(num_blocks, num_kv_heads, block_size, head_dim, block_table,
+                               max_blocks_per_seq, context_lens, batch, num_kv_heads);
+    if (rc) return rc;
+    if (q_starts[0] != 0) return -2;
+    for (int b = 0; b < batch; ++b) if (q_starts[b + 1] < q_starts[b]) return -2;
+    for (int b = 0; b < batch; ++b) {
+        int n = q_starts[b + 1] - q_starts[b];
+        for (int i = 0; i < n; ++i) {
+            int t = context_lens[b] - n + i;
+            if (t < 0) continue;
+            int64_t row = (int64_t)q_starts[b] + i;
+            int64_t p = block_table[(int64_t)b * max_blocks_per_seq + t / block_size];
+            int r = t % block_size;
+            for (int kvh = 0; kvh < num_kv_heads; ++kvh)
+                for (int which = 0; which < 2; ++which) {
+                    const uint16_t* src = (which ? v_new : k_new) + (row * num_kv_heads + kvh) * head_dim;
+                    uint16_t* dst = pool + ((((p * 2 + which) * num_kv_heads + kvh) * block_size + r) * (int64_t)head_dim);
+                    for (int d = 0; d < head_dim; ++d) dst[d] = src[d];
+                }
+            dirty_bitmap[p / 32] |= (uint32_t)1 << (p % 32);
+        }
+    }
+    return 0;
+}

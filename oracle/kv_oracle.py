@@ -69,6 +69,9 @@ def _load():
         lib.kvo_append_tokens.restype = ctypes.c_int
         lib.kvo_append_tokens.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                           u16p, u16p, i32p, ctypes.c_int, i32p, ctypes.c_int, u32p]
+        lib.kvo_append_packed.restype = ctypes.c_int
+        lib.kvo_append_packed.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                          u16p, u16p, i32p, ctypes.c_int, i32p, i32p, ctypes.c_int, u32p]
         lib.kvo_gather_tokens.restype = ctypes.c_int
         lib.kvo_gather_tokens.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                           u16p, u16p, i32p, ctypes.c_int, i32p, ctypes.c_int]
@@ -241,6 +244,32 @@ def append_tokens(pool, k_new, v_new, block_table, positions, dirty_bitmap):
         _ptr(pool, ctypes.c_uint16), NB, Hkv, bs, D, _ptr(k_new, ctypes.c_uint16), _ptr(v_new, ctypes.c_uint16),
         _ptr(block_table, ctypes.c_int32), block_table.shape[1], _ptr(positions, ctypes.c_int32), B,
         _ptr(dirty_bitmap, ctypes.c_uint32)))
+
+
+def append_packed(pool, k_new, v_new, block_table, context_lens, q_starts, dirty_bitmap):
+    """Write the K/V rows of every sequence's newest q_len tokens into the pool (in place) and OR their
+    blocks into dirty_bitmap: the step before prefill_attn, same conventions.
+
+    pool uint16 [NB][2][Hkv][bs][D] (writable), k_new/v_new uint16 [T][Hkv][D] packed in batch order,
+    context_lens int32 [B] (counts the new tokens), q_starts int32 [B + 1].
+    """
+    if not (pool.flags.c_contiguous and pool.flags.writeable and pool.dtype == np.uint16):
+        raise OracleError("pool must be a writable C-contiguous uint16 array")
+    k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
+    block_table, context_lens = _c(block_table, np.int32), _c(context_lens, np.int32)
+    q_starts = _c(q_starts, np.int32)
+    if not (dirty_bitmap.flags.c_contiguous and dirty_bitmap.dtype == np.uint32):
+        raise OracleError("dirty_bitmap must be a C-contiguous uint32 array")
+    NB, two, Hkv, bs, D = pool.shape
+    B = len(context_lens)
+    T = int(q_starts[B]) if q_starts.shape == (B + 1,) else -1
+    if k_new.shape != (T, Hkv, D) or v_new.shape != (T, Hkv, D) or block_table.shape[0] != B \
+            or len(dirty_bitmap) != bitmap_words(NB):
+        raise OracleError("inconsistent shapes")
+    _check(_load().kvo_append_packed(
+        _ptr(pool, ctypes.c_uint16), NB, Hkv, bs, D, _ptr(k_new, ctypes.c_uint16), _ptr(v_new, ctypes.c_uint16),
+        _ptr(block_table, ctypes.c_int32), block_table.shape[1], _ptr(context_lens, ctypes.c_int32),
+        _ptr(q_starts, ctypes.c_int32), B, _ptr(dirty_bitmap, ctypes.c_uint32)))
 
 
 def collect_dirty(dirty_bitmap, num_blocks, clear=True):

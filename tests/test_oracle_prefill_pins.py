@@ -205,3 +205,81 @@ def test_fp8_pool_equals_bf16_pool_holding_the_decoded_values(oracle):
                             k_scale=ks, v_scale=vs)
     b = oracle.prefill_attn(case.q, as_bf16, kv.block_table, kv.context_lens, case.q_starts, g.scale)
     np.testing.assert_allclose(a, b, rtol=1e-15, atol=0)
+
+
+def new_rows(case, seed):
+    g = case.geom
+    ss = np.random.SeedSequence(seed).spawn(2)
+    shape = (case.total_q, g.num_kv_heads, g.head_dim)
+    return W.normal_bf16(ss[0], shape), W.normal_bf16(ss[1], shape)
+
+
+def test_append_packed_matches_numpy_indexing_and_touches_nothing_else(oracle):
+    case = small_prefill(seed=34, lens=(40, 70, 5, 33), q_lens=(40, 17, 1, 0))
+    g, kv = case.geom, case.kv
+    k_new, v_new = new_rows(case, 35)
+    pool = kv.pool.copy()
+    bitmap = np.zeros(oracle.bitmap_words(kv.num_blocks), np.uint32)
+    oracle.append_packed(pool, k_new, v_new, kv.block_table, kv.context_lens, case.q_starts, bitmap)
+    expect = kv.pool.copy()
+    dirty = set()
+    for b in range(case.batch):
+        n, L = int(case.q_lens[b]), int(kv.context_lens[b])
+        for i in range(n):
+            t = L - n + i
+            pid, r = kv.block_table[b, t // g.block_size], t % g.block_size
+            expect[pid, 0, :, r, :] = k_new[case.q_starts[b] + i]
+            expect[pid, 1, :, r, :] = v_new[case.q_starts[b] + i]
+            dirty.add(int(pid))
+    assert np.array_equal(pool, expect)
+    bits = np.unpackbits(bitmap.view(np.uint8), bitorder="little")[:kv.num_blocks]
+    assert set(np.flatnonzero(bits).tolist()) == dirty
+
+
+def test_append_packed_equals_token_by_token_append(oracle):
+    """The packed call is the single-token append applied once per query position."""
+    case = small_prefill(seed=36, lens=(23, 50), q_lens=(9, 17))
+    kv = case.kv
+    k_new, v_new = new_rows(case, 37)
+    a, b_ = kv.pool.copy(), kv.pool.copy()
+    bm_a = np.zeros(oracle.bitmap_words(kv.num_blocks), np.uint32)
+    bm_b = bm_a.copy()
+    oracle.append_packed(a, k_new, v_new, kv.block_table, kv.context_lens, case.q_starts, bm_a)
+    for i in range(int(case.q_lens.max())):
+        positions = np.where(i < case.q_lens, kv.context_lens - case.q_lens + i, -1).astype(np.int32)
+        rows = np.minimum(case.q_starts[:-1] + i, case.total_q - 1)
+        oracle.append_tokens(b_, k_new[rows], v_new[rows], kv.block_table, positions, bm_b)
+    assert np.array_equal(a, b_) and np.array_equal(bm_a, bm_b)
+
+
+def test_append_packed_then_prefill_equals_dense_attention_over_the_new_rows(oracle):
+    case = small_prefill(seed=38, lens=(40, 70), q_lens=(40, 17))
+    kv = case.kv
+    k_new, v_new = new_rows(case, 39)
+    bitmap = np.zeros(oracle.bitmap_words(kv.num_blocks), np.uint32)
+    oracle.append_packed(kv.pool, k_new, v_new, kv.block_table, kv.context_lens, case.q_starts, bitmap)
+    ks, vs = gather_contiguous(kv)
+    for b in range(case.batch):                                       # the tail of each sequence is the new rows
+        n = int(case.q_lens[b])
+        lo, hi = int(case.q_starts[b]), int(case.q_starts[b + 1])
+        assert np.array_equal(ks[b][-n:], W.bf16_bits_to_f32(k_new[lo:hi]).astype(np.float64))
+        assert np.array_equal(vs[b][-n:], W.bf16_bits_to_f32(v_new[lo:hi]).astype(np.float64))
+    np.testing.assert_allclose(run(oracle, case), dense_causal(case), rtol=0, atol=1e-12)
+
+
+def test_append_packed_skips_rows_before_position_zero_and_rejects_bad_input(oracle):
+    case = small_prefill(seed=40, lens=(10,), q_lens=(10,), NB=4)
+    kv = case.kv
+    k_new, v_new = new_rows(case, 41)
+    k13, v13 = np.concatenate([k_new[:3], k_new]), np.concatenate([v_new[:3], v_new])
+    a, b_ = kv.pool.copy(), kv.pool.copy()
+    bm = np.zeros(oracle.bitmap_words(kv.num_blocks), np.uint32)
+    oracle.append_packed(a, k13, v13, kv.block_table, kv.context_lens, np.array([0, 13], np.int32), bm)
+    oracle.append_packed(b_, k_new, v_new, kv.block_table, kv.context_lens, case.q_starts, bm.copy())
+    assert np.array_equal(a, b_)
+    bad = kv.block_table.copy()
+    bad[0, 0] = kv.num_blocks
+    with pytest.raises(oracle.OracleError):
+        oracle.append_packed(a, k_new, v_new, bad, kv.context_lens, case.q_starts, bm)
+    with pytest.raises(oracle.OracleError):
+        oracle.append_packed(a, k_new, v_new, kv.block_table, kv.context_lens, np.array([1, 10], np.int32), bm)
