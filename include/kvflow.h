@@ -225,6 +225,20 @@ int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_
                      int32_t batch, uint32_t* dirty_bitmap, void* stream);
 
 /*
+ * The same for many new tokens per sequence (the K/V rows of recomputed or prefilled tokens), with
+ * kv_prefill_attn's conventions: packed row t = q_starts[b] + i of k_new / v_new
+ * ([total_q][num_kv_heads][head_dim], pool element type) goes to position context_lens[b] - n + i of
+ * sequence b, n = q_starts[b+1] - q_starts[b], and its block is marked dirty.  Rows whose position
+ * would be negative are skipped.  Call it before kv_prefill_attn on the same stream.
+ * Preconditions on device contents as for kv_prefill_attn; q_starts[batch] == total_q.
+ * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, LAUNCH.  batch == 0 or total_q == 0 returns KV_OK without a launch.
+ */
+int kv_append_packed(const kv_pool_desc* pool, const void* k_new, const void* v_new,
+                     const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* context_lens,
+                     const int32_t* q_starts, int32_t batch, int64_t total_q, uint32_t* dirty_bitmap,
+                     void* stream);
+
+/*
  * kv_gather_tokens: the inverse of kv_append_tokens, for replication at token granularity (what
  * a step has written is one row per sequence, not the block around it; over a slow link the
  * difference is a factor of block_size).  For every b with positions[b] >= 0 the K and V rows at

@@ -284,6 +284,23 @@ int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_
     return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }
 
+int kv_append_packed(const kv_pool_desc* pool, const void* k_new, const void* v_new,
+                     const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* context_lens,
+                     const int32_t* q_starts, int32_t batch, int64_t total_q, uint32_t* dirty_bitmap, void* stream)
+{
+    int rc = check_pool(pool);
+    if (rc != KV_OK) return rc;
+    if (batch < 0 || max_blocks_per_seq <= 0 || total_q < 0) return KV_ERR_SHAPE;
+    if (batch == 0 || total_q == 0) return KV_OK;
+    if (!k_new || !v_new || !block_table || !context_lens || !q_starts || !dirty_bitmap) return KV_ERR_NULL;
+    if (!aligned16(k_new) || !aligned16(v_new)) return KV_ERR_ALIGN;
+    hipError_t e = launch_append_packed(pool->base, k_new, v_new, block_table, max_blocks_per_seq, context_lens,
+                                        q_starts, batch, total_q, pool->num_kv_heads, pool->block_size,
+                                        (int)(pool->head_dim * elt_bytes_of(pool)), dirty_bitmap,
+                                        (hipStream_t)stream);
+    return e == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
+}
+
 int kv_gather_tokens(void* k_out, void* v_out, const kv_pool_desc* pool, const int32_t* block_table,
                      int32_t max_blocks_per_seq, const int32_t* positions, int32_t batch, void* stream)
 {

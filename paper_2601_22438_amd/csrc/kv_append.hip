@@ -42,6 +42,43 @@ __global__ __launch_bounds__(kAppendThreads) void append_tokens_kernel(
     if (c == 0) atomicOr(dirty_bitmap + (p >> 5), 1u << (p & 31));
 }
 
+// Many new tokens per sequence (recomputation / prefill): packed row t belongs to the sequence b with
+// q_starts[b] <= t < q_starts[b + 1] and goes to position context_lens[b] - q_len_b + (t - q_starts[b]).
+__global__ __launch_bounds__(kAppendThreads) void append_packed_kernel(
+    char* __restrict__ pool, const char* __restrict__ k_new, const char* __restrict__ v_new,
+    const int32_t* __restrict__ block_table, int max_blocks_per_seq, const int32_t* __restrict__ context_lens,
+    const int32_t* __restrict__ q_starts, int batch, int64_t total_q, int num_kv_heads, int block_size,
+    int block_shift, int row_bytes, uint32_t* __restrict__ dirty_bitmap)
+{
+    const int chunks_per_row = row_bytes / 16;
+    const int chunks_per_tok = 2 * num_kv_heads * chunks_per_row;
+    const int64_t idx = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;
+    if (idx >= total_q * chunks_per_tok) return;
+    const int64_t row = idx / chunks_per_tok;
+    const int c = (int)(idx % chunks_per_tok);
+    int lo = 0, hi = batch;                                           // q_starts[lo] <= row < q_starts[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (q_starts[mid] <= row) lo = mid; else hi = mid;
+    }
+    // sequences without query tokens share their start with the next one: step over them
+    while (q_starts[lo + 1] <= row && lo + 1 < batch) ++lo;
+    const int b = lo;
+    const int first = q_starts[b], n = q_starts[b + 1] - first;
+    if (row >= (int64_t)first + n) return;                            // q_starts[batch] < total_q: no owner
+    const int t = context_lens[b] - n + (int)(row - first);
+    if (t < 0) return;                                                // more new tokens than the context holds
+    const int which = c / (num_kv_heads * chunks_per_row);            // 0 = K, 1 = V
+    const int kvh = (c / chunks_per_row) % num_kv_heads;
+    const int ch = c % chunks_per_row;
+    const int64_t p = block_table[(int64_t)b * max_blocks_per_seq + (t >> block_shift)];
+    const int r = t & (block_size - 1);
+    const char* src = (which ? v_new : k_new) + (row * num_kv_heads + kvh) * row_bytes + ch * 16;
+    char* dst = pool + ((((p * 2 + which) * num_kv_heads + kvh) * block_size + r) * (int64_t)row_bytes) + ch * 16;
+    *(u32x4*)dst = *(const u32x4*)src;
+    if (c == 0) atomicOr(dirty_bitmap + (p >> 5), 1u << (p & 31));
+}
+
 // The inverse direction for token-granular replication: the rows at positions[b] leave the pool
 // for contiguous arrays (what travels is the new token, not the block around it).
 __global__ __launch_bounds__(kAppendThreads) void gather_tokens_kernel(
@@ -118,6 +155,21 @@ hipError_t launch_append_tokens(void* pool, const void* k_new, const void* v_new
     hipLaunchKernelGGL(append_tokens_kernel, dim3((uint32_t)groups), dim3(kAppendThreads), 0, stream, (char*)pool,
                        (const char*)k_new, (const char*)v_new, block_table, max_blocks_per_seq, positions, batch,
                        num_kv_heads, block_size, block_size == 16 ? 4 : 5, row_bytes, dirty_bitmap);
+    return hipGetLastError();
+}
+
+hipError_t launch_append_packed(void* pool, const void* k_new, const void* v_new, const int32_t* block_table,
+                                int max_blocks_per_seq, const int32_t* context_lens, const int32_t* q_starts,
+                                int batch, int64_t total_q, int num_kv_heads, int block_size, int row_bytes,
+                                uint32_t* dirty_bitmap, hipStream_t stream)
+{
+    const int64_t threads = total_q * 2 * num_kv_heads * (row_bytes / 16);
+    const int64_t groups = (threads + kAppendThreads - 1) / kAppendThreads;
+    if (groups > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(append_packed_kernel, dim3((uint32_t)groups), dim3(kAppendThreads), 0, stream, (char*)pool,
+                       (const char*)k_new, (const char*)v_new, block_table, max_blocks_per_seq, context_lens,
+                       q_starts, batch, total_q, num_kv_heads, block_size, block_size == 16 ? 4 : 5, row_bytes,
+                       dirty_bitmap);
     return hipGetLastError();
 }
 

@@ -83,6 +83,11 @@ hipError_t launch_append_tokens(void* pool, const void* k_new, const void* v_new
                                 int batch, int num_kv_heads, int block_size, int row_bytes,
                                 uint32_t* dirty_bitmap, hipStream_t stream);
 
+hipError_t launch_append_packed(void* pool, const void* k_new, const void* v_new, const int32_t* block_table,
+                                int max_blocks_per_seq, const int32_t* context_lens, const int32_t* q_starts,
+                                int batch, int64_t total_q, int num_kv_heads, int block_size, int row_bytes,
+                                uint32_t* dirty_bitmap, hipStream_t stream);
+
 hipError_t launch_gather_tokens(const void* pool, void* k_out, void* v_out, const int32_t* block_table,
                                 int max_blocks_per_seq, const int32_t* positions, int batch, int num_kv_heads,
                                 int block_size, int row_bytes, hipStream_t stream);

@@ -68,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.kv_pack_blocks_counted.argtypes = [P, PD, P, P, I64, P]
     lib.kv_append_tokens.restype = ctypes.c_int
     lib.kv_append_tokens.argtypes = [PD, P, P, P, I32, P, I32, P, P]
+    lib.kv_append_packed.restype = ctypes.c_int
+    lib.kv_append_packed.argtypes = [PD, P, P, P, I32, P, P, I32, I64, P, P]
     lib.kv_gather_tokens.restype = ctypes.c_int
     lib.kv_gather_tokens.argtypes = [P, P, PD, P, I32, P, I32, P]
     lib.kv_collect_dirty.restype = ctypes.c_int
@@ -202,6 +204,14 @@ def kv_append_tokens(pool, k_new, v_new, block_table, positions, dirty_bitmap, s
     _check(load().kv_append_tokens(ctypes.byref(pool_desc(pool)), _ptr(k_new), _ptr(v_new), _ptr(block_table),
                                    block_table.shape[1], _ptr(positions), positions.numel(),
                                    _ptr(dirty_bitmap), _stream_handle(stream)))
+
+
+def kv_append_packed(pool, k_new, v_new, block_table, context_lens, q_starts, dirty_bitmap, stream=None) -> None:
+    """Enqueue the write of every sequence's newest q_len K/V rows (packed, [T][Hkv][D]) and the update of
+    the dirty bitmap; same conventions as kv_prefill_attn."""
+    _check(load().kv_append_packed(ctypes.byref(pool_desc(pool)), _ptr(k_new), _ptr(v_new), _ptr(block_table),
+                                   block_table.shape[1], _ptr(context_lens), _ptr(q_starts), context_lens.numel(),
+                                   k_new.shape[0], _ptr(dirty_bitmap), _stream_handle(stream)))
 
 
 def kv_gather_tokens(k_out, v_out, pool, block_table, positions, stream=None) -> None:

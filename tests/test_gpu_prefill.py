@@ -288,3 +288,60 @@ def test_validate_prefill_catches_bad_device_contents():
     dec = dev.q_starts.clone()
     dec[2] = dec[1] - 1
     assert kvflow.kv_validate_prefill(*args(starts=dec)) == -7
+
+
+# ---- writing the recomputed tokens' K/V rows (the step before the attention call)
+def packed_rows(case, seed, fp8=False):
+    g = case.geom
+    ss = np.random.SeedSequence(seed).spawn(2)
+    shape = (case.total_q, g.num_kv_heads, g.head_dim)
+    gen = (lambda s: W.normal_fp8(s, shape, W.FP8_KV_SCALE)) if fp8 else (lambda s: W.normal_bf16(s, shape))
+    return gen(ss[0]), gen(ss[1])
+
+
+@pytest.mark.parametrize("geom", [(8, 2, 64, 16), (32, 8, 128, 16), (16, 2, 128, 32)])
+def test_append_packed_is_bit_exact_and_marks_the_blocks(oracle, geom):
+    Hq, Hkv, D, bs = geom
+    g = W.Geometry(Hq, Hkv, D, bs)
+    lens = np.array([1, 33, 97, 300, 200, 64], np.int32)
+    q_lens = np.array([1, 33, 64, 300, 0, 17], np.int32)
+    case = W.make_prefill_case("append_packed", 95 + Hq, g, lens, q_lens, max_blocks_per_seq=-(-300 // bs), dirty="last")
+    kv = case.kv
+    k_new, v_new = packed_rows(case, 96)
+    want_pool = kv.pool.copy()
+    want_bm = np.zeros(oracle.bitmap_words(kv.num_blocks), np.uint32)
+    want_bm[0] = 0x5                                                  # bits that are already set must survive
+    oracle.append_packed(want_pool, k_new, v_new, kv.block_table, kv.context_lens, case.q_starts, want_bm)
+    dev = DevicePrefill(case)
+    bm = torch.zeros(len(want_bm), dtype=torch.int32, device="cuda")
+    bm[0] = 0x5
+    kvflow.kv_append_packed(dev.pool, U.bf16_tensor(k_new), U.bf16_tensor(v_new), dev.block_table, dev.context_lens,
+                            dev.q_starts, bm)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.bits_of(dev.pool), want_pool)
+    assert np.array_equal(bm.cpu().numpy().view(np.uint32), want_bm)
+
+
+def test_append_packed_then_recompute_matches_the_oracle_flow(oracle):
+    """FP8 pool: rows are moved as bytes; then the attention call reads what was just written (same stream)."""
+    g = W.Geometry(8, 2, 128, 16, kv_elt_bytes=1)
+    case = W.make_prefill_case("flow", 97, g, np.array([500, 130], np.int32), np.array([260, 130], np.int32),
+                               max_blocks_per_seq=32, dirty="last")
+    kv = case.kv
+    k_new, v_new = packed_rows(case, 98, fp8=True)
+    # the oracle's append moves 16-bit elements; an FP8 row is moved as head_dim/2 of them
+    pool16 = kv.pool.view(np.uint16).copy()
+    bm_want = np.zeros(oracle.bitmap_words(kv.num_blocks), np.uint32)
+    oracle.append_packed(pool16, k_new.view(np.uint16), v_new.view(np.uint16), kv.block_table, kv.context_lens,
+                         case.q_starts, bm_want)
+    want_pool = pool16.view(np.uint8)
+    want = oracle.prefill_attn(case.q, want_pool, kv.block_table, kv.context_lens, case.q_starts, g.scale,
+                               k_scale=0.25, v_scale=0.25)
+    dev = DevicePrefill(case, k_scale=0.25, v_scale=0.25)
+    bm = torch.zeros(len(bm_want), dtype=torch.int32, device="cuda")
+    kvflow.kv_append_packed(dev.pool, torch.from_numpy(k_new).cuda(), torch.from_numpy(v_new).cuda(), dev.block_table,
+                            dev.context_lens, dev.q_starts, bm)
+    got = dev.run()
+    assert np.array_equal(dev.pool.data.cpu().numpy(), want_pool)
+    assert np.array_equal(bm.cpu().numpy().view(np.uint32), bm_want)
+    U.assert_close_to_oracle(got, want, "append + recompute, fp8")

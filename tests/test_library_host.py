@@ -192,3 +192,16 @@ def test_prefill_key_split_suggestion():
     assert kvflow.kv_prefill_key_splits(1, 32, 8, 256, 1024) == 2
     assert kvflow.kv_prefill_key_splits(1, 32, 8, 64, 300) == 1
     assert kvflow.kv_prefill_key_splits(0, 32, 8, 256, 1024) == 0 and kvflow.kv_prefill_key_splits(1, 33, 8, 256, 1024) == 0
+
+
+def test_append_packed_rejects_bad_arguments_before_any_launch(lib):
+    from paper_2601_22438_amd import kvflow
+    ok = desc(kvflow)
+    ap = lambda p=ok, k=0x20000, v=0x30000, tb=0x40000, mb=4, lens=0x50000, qs=0x60000, b=2, tq=10, bm=0x70000: \
+        lib.kv_append_packed(ctypes.byref(p), k, v, tb, mb, lens, qs, b, tq, bm, None)
+    assert ap(b=0) == 0 and ap(tq=0) == 0
+    assert ap(k=0) == -1 and ap(v=0) == -1 and ap(tb=0) == -1 and ap(lens=0) == -1 and ap(qs=0) == -1 and ap(bm=0) == -1
+    assert ap(p=desc(kvflow, base=0)) == -1
+    assert ap(b=-1) == -2 and ap(mb=0) == -2 and ap(tq=-1) == -2
+    assert ap(p=desc(kvflow, d=48)) == -3
+    assert ap(k=0x20008) == -4 and ap(v=0x30004) == -4
