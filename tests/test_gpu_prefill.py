@@ -345,3 +345,26 @@ def test_append_packed_then_recompute_matches_the_oracle_flow(oracle):
     assert np.array_equal(dev.pool.data.cpu().numpy(), want_pool)
     assert np.array_equal(bm.cpu().numpy().view(np.uint32), bm_want)
     U.assert_close_to_oracle(got, want, "append + recompute, fp8")
+
+
+@pytest.mark.parametrize("key_splits", [1, 4])
+def test_large_scores_rising_and_falling_maximum(oracle, key_splits):
+    """Keys that grow along the context force repeated raises of the running maximum; keys that shrink
+    leave it far above the later scores.  Also a future key with a huge score that no query may see."""
+    g = W.Geometry(8, 2, 64, 16)
+    case = W.make_prefill_case("rising", 99, g, np.array([300, 150, 200], np.int32), np.array([300, 40, 200], np.int32),
+                               max_blocks_per_seq=20, dirty="last")
+    kv = case.kv
+    kf = W.bf16_bits_to_f32(kv.pool[:, 0]).copy()
+    for b, L in enumerate(kv.context_lens):
+        for t in range(int(L)):
+            pid = kv.block_table[b, t // g.block_size]
+            gain = (0.2 + 0.05 * t) if b < 2 else (12.0 / (1.0 + 0.1 * t))
+            kf[pid, :, t % g.block_size, :] *= gain
+    kv.pool[:, 0] = W.f32_to_bf16_bits(kf)
+    # the last key of sequence 1 is enormous: only the last query sees it, every other query must not feel it
+    pid = kv.block_table[1, 149 // g.block_size]
+    kv.pool[pid, 0, :, 149 % g.block_size, :] = W.f32_to_bf16_bits(
+        W.bf16_bits_to_f32(kv.pool[pid, 0, :, 149 % g.block_size, :]) * np.float32(40.0))
+    want = oracle_out(oracle, case)
+    U.assert_close_to_oracle(DevicePrefill(case).run(key_splits=key_splits), want, f"rising/falling, {key_splits} parts")
