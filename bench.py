@@ -451,6 +451,24 @@ def bench_recompute(args, kvflow, W):
     return out
 
 
+def bench_yardsticks(args, kvflow, W):
+    """What plain streaming kernels reach on this device: the practical ceilings next to the 8 TB/s peak."""
+    import torch
+    nbytes = 4 << 30
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    b.random_(0, 255)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    out = {"bytes": nbytes}
+    for name, fn, traffic in (("read_only", lambda: kvflow.kv_probe_stream(0, sink, b, nbytes), nbytes),
+                              ("write_only", lambda: kvflow.kv_probe_stream(1, a, None, nbytes), nbytes),
+                              ("contiguous_copy", lambda: kvflow.kv_probe_stream(2, a, b, nbytes), 2 * nbytes)):
+        d = time_calls(fn, 10, 3)
+        gbps = traffic / (d["mean_ms"] * 1e-3) / 1e9
+        out[name] = {**d, "traffic_GBps": gbps, "frac_hbm_peak": gbps / HBM_PEAK_GBPS}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -459,7 +477,7 @@ def main():
     ap.add_argument("--copy-iters", type=int, default=5)
     ap.add_argument("--recovery-blocks", type=int, default=200_000)
     ap.add_argument("--only-timed", action="store_true", help="skip the extra cases and the CPU baseline")
-    ap.add_argument("--extras", default="replication_mix,long_context_fp8_pool,llama8b_layer,recovery,recompute",
+    ap.add_argument("--extras", default="yardsticks,replication_mix,long_context_fp8_pool,llama8b_layer,recovery,recompute",
                     help="comma-separated extra cases to run after the timed workload")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after timing, run one plain device copy of the pool (known size) so that a "
@@ -522,6 +540,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.only_timed:
         runners = {
+            "yardsticks": lambda: bench_yardsticks(args, kvflow, W),
             "replication_mix": lambda: bench_replication_mix(args, kvflow, W),
             "long_context_fp8_pool": lambda: bench_long_context_fp8(args, kvflow, W),
             "llama8b_layer": lambda: bench_llama_layer(args, kvflow, W),

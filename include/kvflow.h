@@ -288,6 +288,16 @@ int kv_validate_prefill(const kv_pool_desc* pool, const int32_t* block_table, in
                         const int32_t* context_lens, const int32_t* q_starts, int32_t batch,
                         int32_t max_q_len, int64_t total_q, void* stream);
 
+/*
+ * HBM yardsticks for roofline tables (for callers that measure: benchmarks, bring-up): one plain
+ * streaming kernel over `bytes` bytes (a multiple of 16) with 16-byte non-temporal accesses.
+ *   mode 0  read b once; a points at >= 16 writable bytes that are left untouched
+ *   mode 1  write a once (contents unspecified)
+ *   mode 2  a <- b, contiguous copy
+ * a, b: device pointers, 16-byte aligned, must not overlap.  Errors: SHAPE, NULL, ALIGN, LAUNCH.
+ */
+int kv_probe_stream(int32_t mode, void* a, const void* b, size_t bytes, void* stream);
+
 /* Static, human-readable text for a kv_status value. */
 const char* kv_status_string(int status);
 

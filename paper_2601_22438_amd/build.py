@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libkvflow.so")
 SOURCES = ["kv_api.hip", "kv_copy.hip", "kv_decode.hip", "kv_decode_fp8.hip", "kv_append.hip",
-           "kv_prefill.hip"]
+           "kv_prefill.hip", "kv_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",

@@ -1,0 +1,80 @@
+// Yardsticks for the roofline tables: what plain streaming kernels (read only, write only, contiguous
+// copy) reach on the device at hand, with the same access style as the product kernels (16-byte
+// accesses, non-temporal policy).  Diagnostics only; nothing else in the library uses them.
+
+#include "kv_internal.h"
+
+namespace kvflow {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kProbeThreads = 256;
+constexpr int kReadUnroll = 8;                        // 16-byte loads in flight per lane
+constexpr int kReadGroups = 256 * 8;                  // persistent grid for the read: 8 workgroups per compute unit
+constexpr int kMoveUnroll = 4;                        // write / copy: one workgroup per 16 KiB, as the pack kernel
+
+// Reads n 16-byte vectors.  The reduction decides a store that needs one particular 128-bit value, so
+// the loads cannot be removed and the sink is, for every practical purpose, never written.
+__global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const u32x4* __restrict__ src, size_t n,
+                                                                   u32x4* __restrict__ sink)
+{
+    const size_t stride = (size_t)gridDim.x * kProbeThreads * kReadUnroll;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (size_t base = (size_t)blockIdx.x * kProbeThreads * kReadUnroll + threadIdx.x; base < n; base += stride) {
+        u32x4 r[kReadUnroll];
+#pragma unroll
+        for (int u = 0; u < kReadUnroll; ++u) {
+            const size_t v = base + (size_t)u * kProbeThreads;
+            r[u] = v < n ? __builtin_nontemporal_load(src + v) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < kReadUnroll; ++u) acc ^= r[u];
+    }
+    if (acc.x == 0x9E3779B9u && acc.y == 0x7F4A7C15u && acc.z == 0xF39CC060u && acc.w == 0x5CEDC834u) sink[0] = acc;
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(u32x4* __restrict__ dst, size_t n)
+{
+    const size_t base = (size_t)blockIdx.x * kProbeThreads * kMoveUnroll + threadIdx.x;
+    const u32x4 val = {blockIdx.x, threadIdx.x, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < kMoveUnroll; ++u) {
+        const size_t v = base + (size_t)u * kProbeThreads;
+        if (v < n) __builtin_nontemporal_store(val, dst + v);
+    }
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(u32x4* __restrict__ dst,
+                                                                   const u32x4* __restrict__ src, size_t n)
+{
+    const size_t base = (size_t)blockIdx.x * kProbeThreads * kMoveUnroll + threadIdx.x;
+    u32x4 r[kMoveUnroll];
+#pragma unroll
+    for (int u = 0; u < kMoveUnroll; ++u) {
+        const size_t v = base + (size_t)u * kProbeThreads;
+        r[u] = v < n ? __builtin_nontemporal_load(src + v) : u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < kMoveUnroll; ++u) {
+        const size_t v = base + (size_t)u * kProbeThreads;
+        if (v < n) __builtin_nontemporal_store(r[u], dst + v);
+    }
+}
+
+hipError_t launch_probe(int mode, void* a, const void* b, size_t bytes, hipStream_t stream)
+{
+    const size_t n = bytes / 16;
+    const size_t per_group = (size_t)kProbeThreads * kMoveUnroll;
+    const size_t groups = (n + per_group - 1) / per_group;
+    if (groups > 0x7FFFFFFFu) return hipErrorInvalidValue;
+    const dim3 block(kProbeThreads);
+    if (mode == 0)
+        hipLaunchKernelGGL(probe_read_kernel, dim3(kReadGroups), block, 0, stream, (const u32x4*)b, n, (u32x4*)a);
+    else if (mode == 1)
+        hipLaunchKernelGGL(probe_write_kernel, dim3((uint32_t)groups), block, 0, stream, (u32x4*)a, n);
+    else
+        hipLaunchKernelGGL(probe_copy_kernel, dim3((uint32_t)groups), block, 0, stream, (u32x4*)a, (const u32x4*)b, n);
+    return hipGetLastError();
+}
+
+}  // namespace kvflow

@@ -80,6 +80,8 @@ def load() -> ctypes.CDLL:
     lib.kv_validate_prefill.argtypes = [PD, P, I32, P, P, I32, I32, I64, P]
     lib.kv_validate_block_ids.restype = ctypes.c_int
     lib.kv_validate_block_ids.argtypes = [PD, P, I64, I32, P]
+    lib.kv_probe_stream.restype = ctypes.c_int
+    lib.kv_probe_stream.argtypes = [I32, P, P, SZ, P]
     lib.kv_status_string.restype, lib.kv_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
     _lib = lib
     return lib
@@ -224,6 +226,11 @@ def kv_collect_dirty(dirty_bitmap, num_blocks, dirty_ids, dirty_count, clear=Tru
     """Enqueue bitmap -> ascending id list (dirty_ids) and its length (dirty_count[0]), both on the device."""
     _check(load().kv_collect_dirty(_ptr(dirty_bitmap), int(num_blocks), _ptr(dirty_ids), dirty_ids.numel(),
                                    _ptr(dirty_count), int(bool(clear)), _stream_handle(stream)))
+
+
+def kv_probe_stream(mode, a, b, nbytes, stream=None) -> None:
+    """Enqueue one plain streaming kernel: mode 0 reads b, 1 writes a, 2 copies b to a (nbytes, multiple of 16)."""
+    _check(load().kv_probe_stream(int(mode), _ptr(a), _ptr(b), int(nbytes), _stream_handle(stream)))
 
 
 def kv_validate_decode(pool, block_table, context_lens, max_context_len, stream=None) -> int:

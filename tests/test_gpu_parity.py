@@ -259,3 +259,18 @@ def test_decode_large_scores_and_rising_maximum(oracle):
     dc = DeviceCase(case)
     for wgs in (0, 1):
         assert_close_to_oracle(dc.decode(torch.float32, workgroups=wgs), want, f"rising max workgroups={wgs}")
+
+
+def test_streaming_probes_copy_exactly_and_leave_the_sink_alone():
+    n = (1 << 22) + 16 * 37                                         # not a multiple of the kernels' stride
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+    kvflow.kv_probe_stream(2, dst, src, n)
+    sink = torch.full((16,), 7, dtype=torch.uint8, device="cuda")
+    kvflow.kv_probe_stream(0, sink, src, n)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and torch.all(dst[n:] == 0)
+    assert torch.all(sink == 7)
+    kvflow.kv_probe_stream(1, dst, None, n)                         # contents unspecified, bounds are not
+    torch.cuda.synchronize()
+    assert torch.all(dst[n:] == 0)
