@@ -12,8 +12,10 @@ constexpr int kTileTokens = 32;
 // Decode workgroup: 4 independent wavefronts.
 constexpr int kDecodeWaves = 4;
 constexpr int kDecodeThreads = kDecodeWaves * 64;
-// Persistent decode grid that fills the chip: 256 compute units x 2 resident workgroups.
-constexpr int kDecodeMaxWorkgroups = 512;
+// Persistent decode grid that fills the chip: one workgroup per compute unit (256).  Measured: 4
+// wavefronts per compute unit with 16 KiB in flight each already saturate HBM, and a second resident
+// workgroup only adds records and contention (2-5 points slower on every case).
+constexpr int kDecodeMaxWorkgroups = 256;
 // A run shorter than this many tiles is not worth its record traffic: small problems get fewer runs.
 constexpr int kDecodeMinTilesPerRun = 4;
 // Sequences handled by one launch (their tile counts are scanned in LDS); larger batches are sliced.

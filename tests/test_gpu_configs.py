@@ -62,7 +62,7 @@ def test_long_context_sampled_rows_and_pack(oracle):
     case = W.long_context()
     g = case.geom
     dc = DeviceCase(case)
-    assert kvflow.kv_decode_workgroups(case.batch, g.num_kv_heads, case.max_context_len) == 512
+    assert kvflow.kv_decode_workgroups(case.batch, g.num_kv_heads, case.max_context_len) == 256
     rows = sample_rows(case, 24, seed=5)
     for dt in (torch.bfloat16, torch.float32):
         got = dc.decode(dt)

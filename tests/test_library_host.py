@@ -100,12 +100,12 @@ def test_block_bytes_workgroups_and_workspace_size(lib):
     assert lib.kv_block_bytes(None) == 0
     # small problems get fewer workgroups, big ones the full persistent grid; a request is honoured
     assert kvflow.kv_decode_workgroups(4, 2, 256) == 4
-    assert kvflow.kv_decode_workgroups(8, 8, 65536) == 512
+    assert kvflow.kv_decode_workgroups(8, 8, 65536) == 256
     assert kvflow.kv_decode_workgroups(8, 8, 65536, 100) == 100
     assert kvflow.kv_decode_workgroups(0, 8, 65536) == 0
     assert kvflow.kv_decode_workgroups(8, 8, 65536, -3) == 0
     # workspace = tile counts (16-byte padded) + (runs + rows) * group * (D + 4) floats
-    wgs = 512
+    wgs = 256
     want = 48 + (wgs * 4 + 8 * 8) * 4 * (128 + 4) * 4      # 9 counts = 36 bytes, padded to 48
     assert kvflow.kv_decode_workspace_bytes(8, 32, 8, 128, 65536) == want
     assert kvflow.kv_decode_workspace_bytes(8, 33, 8, 128, 65536) == 0
