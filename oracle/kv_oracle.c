@@ -7,13 +7,13 @@
  *   - decode attention of one query token per sequence over that sequence's
  *     cached keys/values, where the cache is stored as fixed-size blocks that a
  *     per-sequence block table maps from logical to physical position.  This is
- *     the "block representation of KV cache" that Sec. 3.2 item 3 (Background
- *     KV Cache Replication) of the paper builds on; the attention formula is
+ *     the block-structured cache that Sec. 3.2 item 3 (background replication
+ *     of the KV cache) of the paper builds on; the attention formula is
  *     the textbook scaled dot-product attention with grouped query heads
  *     (consecutive query heads share one KV head).
  *   - block-by-block replication (Sec. 3.2 item 3, Sec. 4.4): gather listed
  *     pool blocks into a contiguous replica, and the inverse used when a
- *     replication target continues requests "from the replicated state".
+ *     replication target takes over requests and continues them from its copy.
  *
  * All floating point is IEEE double.  Inputs are bf16 bit patterns (uint16)
  * widened exactly: bf16 -> fp32 by a 16-bit left shift -> double.  The pool may
@@ -227,7 +227,7 @@ int kvo_restore_blocks(uint8_t* pool, const uint8_t* replica, int64_t block_byte
 
 /*
  * Writing a step's new tokens into the pool and tracking the blocks that became dirty (the
- * blocks "a step has written", which background replication then ships block by block;
+ * blocks that hold new tokens, which background replication then ships block by block;
  * Sec. 3.2 item 3).  One new token per sequence: sequence b's K/V rows (all KV heads) go to
  * position positions[b] of its context, i.e. to row positions[b] % bs of physical block
  * block_table[b][positions[b] / bs]; positions[b] < 0 means the sequence takes no token.

@@ -117,16 +117,12 @@ def test_fp8_pack_restore_and_append_bitwise(oracle):
     assert np.array_equal(bm_d.cpu().numpy().view(np.uint32), bm_h)
 
 
-def test_fp8_long_context_sampled_rows(oracle):
+def test_fp8_long_context_every_row(oracle):
+    """Every output element against the oracle (its pass over this case takes a few seconds)."""
     case = W.long_context(kv_elt_bytes=1)
     g = case.geom
     assert case.kv_bytes == int(case.context_lens.sum()) * 2 * g.num_kv_heads * g.head_dim
     dc = DeviceCase(case, k_scale=KS, v_scale=VS)
-    rng = np.random.default_rng(5)
-    flat = rng.choice(case.batch * g.num_q_heads, size=20, replace=False)
-    rows = np.stack([flat // g.num_q_heads, flat % g.num_q_heads], axis=1).astype(np.int32)
-    want = oracle_decode(oracle, case, rows=rows)
+    want = oracle_decode(oracle, case)
     for dt in (torch.bfloat16, torch.float32):
-        got = dc.decode(dt)
-        sub = got[torch.from_numpy(rows[:, 0]).long().cuda(), torch.from_numpy(rows[:, 1]).long().cuda()]
-        assert_close_to_oracle(sub, want, f"fp8 long_context {dt}")
+        assert_close_to_oracle(dc.decode(dt), want, f"fp8 long_context {dt}")

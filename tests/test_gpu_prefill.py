@@ -53,10 +53,8 @@ def test_prefill_tiny_matches_oracle(oracle):
     want = oracle_out(oracle, case)
     dev = DevicePrefill(case)
     U.assert_close_to_oracle(dev.run(torch.float32), want, "fp32 out")
-    got16 = dev.run(torch.bfloat16)
-    # bf16 output: the fp32 result rounded once more
-    err = np.abs(got16.double().cpu().numpy() - want)
-    assert err.max() <= U.MAX_ABS + 2.0 ** -8 * np.abs(want).max()
+    # bf16 output: the fp32 result rounded once more (half an ulp of |x| < 4 is 2^-7), same gates
+    U.assert_close_to_oracle(dev.run(torch.bfloat16), want, "bf16 out")
 
 
 # (Hq, Hkv, D, bs): groups of 1, 2, 3, 4, 8 and 16 query heads per KV head, both head sizes and block sizes
@@ -162,10 +160,13 @@ def sample_rows(case, n_rows, seed):
     return np.array(rows, np.int32)
 
 
-@pytest.mark.parametrize("maker", [W.recompute, W.chunked_recompute])
-def test_full_size_cases_on_sampled_rows(oracle, maker):
+# The oracle needs ~1e12 fp64 multiply-adds for every row of `recompute` and ~5e12 for
+# `chunked_recompute` (minutes to tens of minutes on 16 host cores), so these two cases are checked
+# on sampled rows: the first and last query of every sequence plus 2000 / 1000 uniformly drawn rows.
+@pytest.mark.parametrize("maker,n_rows", [(W.recompute, 2000), (W.chunked_recompute, 1000)])
+def test_full_size_cases_on_sampled_rows(oracle, maker, n_rows):
     case = maker()
-    rows = sample_rows(case, 200, 58)
+    rows = sample_rows(case, n_rows, 58)
     want = oracle_out(oracle, case, rows=rows)
     got = DevicePrefill(case).run(torch.float32, canary_rows=1)
     pick = got[torch.from_numpy(rows[:, 0].astype(np.int64)).cuda(), torch.from_numpy(rows[:, 1].astype(np.int64)).cuda()]
@@ -223,8 +224,7 @@ def test_key_splits_match_oracle_on_ragged_cases(oracle, key_splits):
     want = oracle_out(oracle, case)
     dev = DevicePrefill(case)
     U.assert_close_to_oracle(dev.run(key_splits=key_splits), want, f"tiny, {key_splits} parts")
-    got16 = dev.run(torch.bfloat16, key_splits=key_splits)
-    assert np.abs(got16.double().cpu().numpy() - want).max() <= U.MAX_ABS + 2.0 ** -8 * np.abs(want).max()
+    U.assert_close_to_oracle(dev.run(torch.bfloat16, key_splits=key_splits), want, f"tiny bf16, {key_splits} parts")
 
 
 @pytest.mark.parametrize("geom", [(4, 4, 128, 16), (6, 2, 64, 16), (16, 2, 128, 32)])

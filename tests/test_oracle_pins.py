@@ -529,6 +529,51 @@ def test_fp8_scales_act_as_score_scale_and_output_factor(oracle):
             assert np.array_equal(got[b, h], v[one.block_table[b, 0], 1, h // one.geom.group, 0])
 
 
+def test_fp8_every_code_through_the_oracles_own_decoder(oracle):
+    """All 256 E4M3 codes go through the C oracle's decoder, on the V side and on the K side, against
+    torch's float8_e4m3fn cast: exponent field 15 holds ordinary numbers up to 448 (no infinities), and
+    only mantissa 7 of it is NaN, which propagates into the output row that touches it."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    nan = np.isnan(lib)
+    assert nan.tolist() == [c in (0x7F, 0xFF) for c in range(256)]
+    D, Hkv, bs = 64, 4, 16
+    # V side: one cached token whose V rows (4 KV heads x 64 channels) enumerate the codes; a
+    # single-token context returns V exactly, so out[h] = decode(code) * v_scale.
+    vs = 0.375
+    pool = np.zeros((2, 2, Hkv, bs, D), np.uint8)
+    pool[1, 1, :, 0, :] = codes.reshape(Hkv, D)
+    q = W.normal_bf16(np.random.SeedSequence(91), (1, Hkv, D))
+    table = np.array([[1]], np.int32)
+    got = oracle.decode_attn(q, pool, table, np.array([1], np.int32), 0.125, k_scale=1.0, v_scale=vs)
+    want = (lib * float(np.float32(vs))).reshape(Hkv, D)
+    assert np.array_equal(np.isnan(got[0]), nan.reshape(Hkv, D))
+    assert np.array_equal(got[0][~np.isnan(got[0])], want[~np.isnan(want)])
+    # K side: 256 query heads, head h one-hot at channel h % 64 of KV head h / 64, two cached tokens:
+    # K[0] enumerates the 254 finite codes (zero in place of the two NaN codes), K[1] = 0; V[0] = 1,
+    # V[1] = 0.  Then the score of token 0 is scale * k_scale * decode(code_h), that of token 1 is 0, and
+    # out[h] = logistic(score) in every channel.
+    ks, scale = 0.25, 0.0625                                  # |score| <= 7: far from saturating the logistic
+    pool = np.zeros((1, 2, Hkv, bs, D), np.uint8)
+    pool[0, 0, :, 0, :] = np.where(nan, 0, codes).reshape(Hkv, D)
+    pool[0, 1, :, 0, :] = 0x38                                # 1.0
+    one = W.f32_to_bf16_bits(np.float32([1.0]))[0]
+    qh = np.zeros((1, 256, D), np.uint16)
+    qh[0, np.arange(256), np.arange(256) % D] = one
+    args = (np.array([[0]], np.int32), np.array([2], np.int32), scale)
+    got = oracle.decode_attn(qh, pool, *args, k_scale=ks, v_scale=1.0)[0]
+    score = float(np.float32(scale)) * float(np.float32(ks)) * np.where(nan, 0.0, lib)
+    want = 1.0 / (1.0 + np.exp(-score))
+    np.testing.assert_allclose(got, np.repeat(want[:, None], D, axis=1), rtol=0, atol=1e-15)
+    # a NaN code in a key row reaches every head of its KV head (0 * NaN is NaN) and no other head
+    pool[0, 0, 1, 0, 5] = 0x7F
+    bad = oracle.decode_attn(qh, pool, *args, k_scale=ks, v_scale=1.0)[0]
+    assert np.isnan(bad[64:128]).all() and np.array_equal(bad[:64], got[:64]) and np.array_equal(bad[128:], got[128:])
+    # the largest codes are told apart: 448 is neither infinite nor equal to 416
+    assert got[0x7E, 0] < 1.0 and got[0x7E, 0] > got[0x7D, 0] > got[0x78, 0] > got[0x77, 0]
+
+
 def test_fp8_pack_restore_move_bytes(oracle):
     case = small_fp8_case(seed=77)
     ids = case.dirty_ids
