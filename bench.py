@@ -121,7 +121,7 @@ def bench_long_context(args, kvflow, W):
     ids = torch.from_numpy(case.dirty_ids).cuda()
     replicas = [torch.empty((n,) + pool.shape[1:], dtype=torch.bfloat16, device="cuda") for _ in range(2)]
     # the recovery target: a second pool and fresh ids for the restored blocks
-    target = torch.empty_like(pool)
+    target = torch.zeros_like(pool)
     fresh = np.random.default_rng(12345).permutation(case.num_blocks)[:n].astype(np.int32)
     fresh_ids = torch.from_numpy(fresh).cuda()
     kvflow.kv_pack_blocks(replicas[1], pool, ids)          # the replica the first restore consumes
@@ -176,8 +176,13 @@ def bench_long_context(args, kvflow, W):
     r_ms = stats([e[2].elapsed_time(e[3]) for e in all_evs])
     kv_bytes = case.kv_bytes
     payload = n * g.block_bytes
+    # what the timed steps wrote, kept on the host for the parity figures printed beside the rate
+    written = {"out": dec.out.double().cpu().numpy(),
+               "replicas": [r.view(torch.int16).cpu().numpy().view(np.uint16) for r in replicas],
+               "target": target.view(torch.int16).cpu().numpy().view(np.uint16), "fresh_ids": fresh}
+    del target
     res = {
-        "case": case, "dec": dec, "pool": pool, "ids": ids, "replica": replicas[0],
+        "case": case, "dec": dec, "pool": pool, "ids": ids, "replica": replicas[0], "written": written,
         "ms_per_step": wall / args.steps * 1e3, "graph_ms_per_step": graph_ms,
         "decode": d_ms, "pack": p_ms, "restore": r_ms,
         "kv_bytes": kv_bytes, "payload": payload,
@@ -192,14 +197,14 @@ def cpu_baseline(case, oracle, n_seqs=None):
     n_seqs = case.batch if n_seqs is None else n_seqs
     rows = np.array([(b, h) for b in range(n_seqs) for h in range(g.num_q_heads)], np.int32)
     t0 = time.perf_counter()
-    _, threads = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale,
-                                    rows=rows, return_threads=True)
+    want, threads = oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale,
+                                       rows=rows, return_threads=True)
     dt = time.perf_counter() - t0
     sample_bytes = int(case.context_lens[:n_seqs].astype(np.int64).sum()) * g.kv_bytes_per_token
     t0 = time.perf_counter()
     rep, _ = oracle.pack_blocks(case.pool, case.dirty_ids, return_threads=True)
     dt_pack = time.perf_counter() - t0
-    return {
+    return want.reshape(n_seqs, g.num_q_heads, g.head_dim), rep, {
         "value": sample_bytes / dt / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
         "sample": f"fp64 decode of all {g.num_q_heads} query heads of the first {n_seqs} of {case.batch} "
                   f"sequences of the timed workload ({sample_bytes / 1e6:.0f} MB of KV, {dt:.1f} s); "
@@ -207,6 +212,19 @@ def cpu_baseline(case, oracle, n_seqs=None):
         "seconds": dt, "pack_payload_GBps": rep.nbytes / dt_pack / 1e9,
         "cpu_model": cpu_model(), "host_cores": os.cpu_count(),
     }
+
+
+def parity_of_timed_buffers(case, written, want_out, want_replica, oracle):
+    """The buffers the timed steps wrote against the oracle: decode output element by element, the packed
+    replicas and the restored pool byte for byte."""
+    err = np.abs(written["out"][:len(want_out)] - want_out)
+    want_target = np.zeros_like(case.pool)
+    oracle.restore_blocks(want_target, want_replica, written["fresh_ids"])
+    return {"decode_max_abs": float(err.max()), "decode_mean_abs": float(err.mean()),
+            "decode_rows_checked": int(err.shape[0] * err.shape[1]), "decode_finite": bool(np.isfinite(written["out"]).all()),
+            "pack_bit_exact": bool(all(np.array_equal(r, want_replica) for r in written["replicas"])),
+            "restore_bit_exact": bool(np.array_equal(written["target"], want_target)),
+            "tolerance": {"max_abs": 2e-2, "mean_abs": 2e-3}}
 
 
 def cpu_model():
@@ -521,12 +539,17 @@ def main():
         },
         "paper_context": PAPER_CONTEXT,
     }
-    cpu = None
+    cpu = parity = None
     if not args.only_timed:
         import oracle
         oracle.build()
-        cpu = cpu_baseline(case, oracle)
+        want_out, want_replica, cpu = cpu_baseline(case, oracle)
         log(f"[bench] cpu baseline done: {cpu['value']:.3f} GB/s on {cpu['cores']} threads")
+        parity = parity_of_timed_buffers(case, main_res["written"], want_out, want_replica, oracle)
+        log(f"[bench] parity of the timed buffers: {parity}")
+        if not (parity["decode_max_abs"] <= 2e-2 and parity["decode_mean_abs"] <= 2e-3 and parity["decode_finite"]
+                and parity["pack_bit_exact"] and parity["restore_bit_exact"]):
+            sys.exit(f"bench.py: the timed steps' results do not match the oracle: {parity}")
     if args.calibration_copy:
         src_pool = main_res["pool"]
         dst_pool = torch.empty_like(src_pool)
@@ -535,7 +558,7 @@ def main():
         extra["calibration_copy_bytes"] = src_pool.numel() * 2
         del dst_pool
     # free the timed workload before the large cases
-    for k in ("dec", "pool", "ids", "replica"):
+    for k in ("dec", "pool", "ids", "replica", "written"):
         main_res.pop(k)
     torch.cuda.empty_cache()
     if not args.only_timed:
@@ -565,6 +588,7 @@ def main():
                    "kv_bytes_per_step": main_res["kv_bytes"], "pack_payload_bytes": main_res["payload"]},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "parity": parity,
         "extra": extra,
     }
     print(json.dumps(line), flush=True)

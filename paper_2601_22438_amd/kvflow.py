@@ -106,6 +106,59 @@ def _ptr(t) -> int:
     return 0 if t is None else int(t.data_ptr())
 
 
+# Host-only argument checks (no synchronisation): the kernels read these buffers as raw memory of a
+# fixed element type, so a tensor of another dtype, a strided view or a host tensor would make them
+# follow garbage indices.
+def _dev(t, name, dtype=None, shape=None, numel=None, allow_pinned=False):
+    if not torch.is_tensor(t):
+        raise ValueError(f"{name} must be a torch tensor")
+    if not (t.is_cuda or (allow_pinned and t.is_pinned())):
+        raise ValueError(f"{name} must live in GPU memory" + (" or pinned host memory" if allow_pinned else ""))
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name} must hold at least {numel} elements, got {t.numel()}")
+    return t
+
+
+def _pool_data(pool):
+    return pool.data if isinstance(pool, Fp8Pool) else pool
+
+
+def _table(block_table, batch):
+    _dev(block_table, "block_table", torch.int32)
+    if block_table.dim() != 2 or block_table.shape[0] != batch:
+        raise ValueError(f"block_table must be int32 [batch={batch}][max_blocks_per_seq]")
+    return block_table
+
+
+def _new_rows(pool, k, v, rows):
+    """k, v: [rows][Hkv][D] in the pool's element type."""
+    data = _pool_data(pool)
+    want = (rows, data.shape[2], data.shape[4])
+    for t, name in ((k, "K rows"), (v, "V rows")):
+        _dev(t, name, shape=want)
+        if t.element_size() != data.element_size():
+            raise ValueError(f"{name} must have the pool's element size ({data.element_size()} bytes)")
+
+
+def _bitmap(dirty_bitmap, pool):
+    _dev(dirty_bitmap, "dirty_bitmap", (torch.int32, torch.uint32), numel=(_pool_data(pool).shape[0] + 31) // 32)
+
+
+def _replica(replica, pool, n, name="replica"):
+    _dev(replica, name, allow_pinned=True)
+    data = _pool_data(pool)
+    need = n * data[0].numel() * data.element_size()
+    if replica.numel() * replica.element_size() < need:
+        raise ValueError(f"{name} holds {replica.numel() * replica.element_size()} bytes, {need} needed")
+    return replica
+
+
 class Fp8Pool:
     """An FP8 E4M3 pool: a contiguous uint8 (or float8_e4m3fn) tensor [NB][2][Hkv][bs][D] plus its scales."""
 
@@ -122,8 +175,10 @@ class Fp8Pool:
 def pool_desc(pool) -> kv_pool_desc:
     """Describe a pool of shape [NB][2][Hkv][bs][D]: a bf16 tensor, or an Fp8Pool (contiguous, on the GPU)."""
     data = pool.data if isinstance(pool, Fp8Pool) else pool
-    if data.dim() != 5 or data.shape[1] != 2 or not data.is_contiguous():
+    if not torch.is_tensor(data) or data.dim() != 5 or data.shape[1] != 2 or not data.is_contiguous():
         raise ValueError("pool must be a contiguous [NB][2][Hkv][bs][D] tensor")
+    if not data.is_cuda:
+        raise ValueError("pool must live in GPU memory")
     nb, _, hkv, bs, d = data.shape
     if isinstance(pool, Fp8Pool):
         return kv_pool_desc(data.data_ptr(), nb, hkv, bs, d, KV_DTYPE_FP8_E4M3, pool.k_scale, pool.v_scale)
@@ -149,7 +204,15 @@ def kv_decode_workspace_bytes(batch, num_q_heads, num_kv_heads, head_dim, max_co
 def kv_decode_attn(out, q, pool, block_table, context_lens, max_context_len, scale,
                    num_workgroups=0, workspace=None, stream=None) -> None:
     """Enqueue paged decode attention; ``out`` ([B][Hq][D], bf16 or fp32) is written in place."""
+    _dev(q, "q", torch.bfloat16)
+    if q.dim() != 3 or q.shape[2] != _pool_data(pool).shape[4]:
+        raise ValueError("q must be bf16 [batch][num_q_heads][head_dim of the pool]")
     batch, num_q_heads, _ = q.shape
+    _dev(out, "out", (torch.bfloat16, torch.float32), shape=q.shape)
+    _table(block_table, batch)
+    _dev(context_lens, "context_lens", torch.int32, shape=(batch,))
+    if workspace is not None:
+        _dev(workspace, "workspace")
     out_dtype = {torch.bfloat16: KV_DTYPE_BF16, torch.float32: KV_DTYPE_F32}[out.dtype]
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().kv_decode_attn(
@@ -170,7 +233,17 @@ def kv_prefill_attn(out, q, pool, block_table, context_lens, q_starts, max_q_len
                     workspace=None, stream=None) -> None:
     """Enqueue causal attention of the packed query tokens ``q`` ([T][Hq][D]) over the pool; ``out`` is
     written in place ([T][Hq][D], bf16 or fp32).  ``workspace`` is needed for key_splits > 1."""
+    _dev(q, "q", torch.bfloat16)
+    if q.dim() != 3 or q.shape[2] != _pool_data(pool).shape[4]:
+        raise ValueError("q must be bf16 [total_q][num_q_heads][head_dim of the pool]")
     total_q, num_q_heads, _ = q.shape
+    _dev(out, "out", (torch.bfloat16, torch.float32), shape=q.shape)
+    _dev(context_lens, "context_lens", torch.int32)
+    batch = context_lens.numel()
+    _table(block_table, batch)
+    _dev(q_starts, "q_starts", torch.int32, shape=(batch + 1,))
+    if workspace is not None:
+        _dev(workspace, "workspace")
     out_dtype = {torch.bfloat16: KV_DTYPE_BF16, torch.float32: KV_DTYPE_F32}[out.dtype]
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().kv_prefill_attn(
@@ -183,6 +256,8 @@ def kv_prefill_attn(out, q, pool, block_table, context_lens, q_starts, max_q_len
 def kv_pack_blocks(replica, pool, block_ids, n=None, stream=None) -> None:
     """Enqueue replica[i] <- pool[block_ids[i]] for i < n (default: all of block_ids)."""
     n = block_ids.numel() if n is None else int(n)
+    _dev(block_ids, "block_ids", torch.int32, numel=n)
+    _replica(replica, pool, n)
     _check(load().kv_pack_blocks(_ptr(replica), ctypes.byref(pool_desc(pool)), _ptr(block_ids), n,
                                  _stream_handle(stream)))
 
@@ -190,6 +265,8 @@ def kv_pack_blocks(replica, pool, block_ids, n=None, stream=None) -> None:
 def kv_restore_blocks(pool, replica, block_ids, n=None, stream=None) -> None:
     """Enqueue pool[block_ids[i]] <- replica[i] for i < n (ids pairwise distinct)."""
     n = block_ids.numel() if n is None else int(n)
+    _dev(block_ids, "block_ids", torch.int32, numel=n)
+    _replica(replica, pool, n)
     _check(load().kv_restore_blocks(ctypes.byref(pool_desc(pool)), _ptr(replica), _ptr(block_ids), n,
                                     _stream_handle(stream)))
 
@@ -197,12 +274,19 @@ def kv_restore_blocks(pool, replica, block_ids, n=None, stream=None) -> None:
 def kv_pack_blocks_counted(replica, pool, block_ids, count, max_n=None, stream=None) -> None:
     """Enqueue replica[i] <- pool[block_ids[i]] for i < min(count[0], max_n); count lives on the device."""
     max_n = block_ids.numel() if max_n is None else int(max_n)
+    _dev(block_ids, "block_ids", torch.int32, numel=max_n)
+    _dev(count, "count", torch.int32, numel=1)
+    _replica(replica, pool, max_n)
     _check(load().kv_pack_blocks_counted(_ptr(replica), ctypes.byref(pool_desc(pool)), _ptr(block_ids),
                                          _ptr(count), max_n, _stream_handle(stream)))
 
 
 def kv_append_tokens(pool, k_new, v_new, block_table, positions, dirty_bitmap, stream=None) -> None:
     """Enqueue the write of one new K/V token per sequence and the update of the dirty bitmap."""
+    batch = _dev(positions, "positions", torch.int32).numel()
+    _table(block_table, batch)
+    _new_rows(pool, k_new, v_new, batch)
+    _bitmap(dirty_bitmap, pool)
     _check(load().kv_append_tokens(ctypes.byref(pool_desc(pool)), _ptr(k_new), _ptr(v_new), _ptr(block_table),
                                    block_table.shape[1], _ptr(positions), positions.numel(),
                                    _ptr(dirty_bitmap), _stream_handle(stream)))
@@ -211,6 +295,11 @@ def kv_append_tokens(pool, k_new, v_new, block_table, positions, dirty_bitmap, s
 def kv_append_packed(pool, k_new, v_new, block_table, context_lens, q_starts, dirty_bitmap, stream=None) -> None:
     """Enqueue the write of every sequence's newest q_len K/V rows (packed, [T][Hkv][D]) and the update of
     the dirty bitmap; same conventions as kv_prefill_attn."""
+    batch = _dev(context_lens, "context_lens", torch.int32).numel()
+    _table(block_table, batch)
+    _dev(q_starts, "q_starts", torch.int32, shape=(batch + 1,))
+    _new_rows(pool, k_new, v_new, k_new.shape[0])
+    _bitmap(dirty_bitmap, pool)
     _check(load().kv_append_packed(ctypes.byref(pool_desc(pool)), _ptr(k_new), _ptr(v_new), _ptr(block_table),
                                    block_table.shape[1], _ptr(context_lens), _ptr(q_starts), context_lens.numel(),
                                    k_new.shape[0], _ptr(dirty_bitmap), _stream_handle(stream)))
@@ -218,12 +307,18 @@ def kv_append_packed(pool, k_new, v_new, block_table, context_lens, q_starts, di
 
 def kv_gather_tokens(k_out, v_out, pool, block_table, positions, stream=None) -> None:
     """Enqueue the copy of the K/V rows at positions[b] out of the pool into k_out[b], v_out[b]."""
+    batch = _dev(positions, "positions", torch.int32).numel()
+    _table(block_table, batch)
+    _new_rows(pool, k_out, v_out, batch)
     _check(load().kv_gather_tokens(_ptr(k_out), _ptr(v_out), ctypes.byref(pool_desc(pool)), _ptr(block_table),
                                    block_table.shape[1], _ptr(positions), positions.numel(), _stream_handle(stream)))
 
 
 def kv_collect_dirty(dirty_bitmap, num_blocks, dirty_ids, dirty_count, clear=True, stream=None) -> None:
     """Enqueue bitmap -> ascending id list (dirty_ids) and its length (dirty_count[0]), both on the device."""
+    _dev(dirty_bitmap, "dirty_bitmap", (torch.int32, torch.uint32), numel=(int(num_blocks) + 31) // 32)
+    _dev(dirty_ids, "dirty_ids", torch.int32)
+    _dev(dirty_count, "dirty_count", torch.int32, numel=1)
     _check(load().kv_collect_dirty(_ptr(dirty_bitmap), int(num_blocks), _ptr(dirty_ids), dirty_ids.numel(),
                                    _ptr(dirty_count), int(bool(clear)), _stream_handle(stream)))
 

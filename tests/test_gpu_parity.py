@@ -202,6 +202,41 @@ def test_validate_helpers_catch_bad_device_contents():
     assert kvflow.kv_validate_block_ids(dc.pool, ids, require_distinct=True) == -7
 
 
+def test_binding_rejects_wrong_dtype_layout_and_shape():
+    """Index arrays of torch's default int64, strided views and mismatched shapes are refused on the host
+    (the kernels would read them as raw int32 / bf16 memory)."""
+    case = W.tiny()
+    dc = DeviceCase(case)
+    g = case.geom
+    out = torch.empty((case.batch, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda")
+    ws = torch.empty(kvflow.kv_decode_workspace_bytes(case.batch, g.num_q_heads, g.num_kv_heads, g.head_dim,
+                                                      dc.max_len) // 4, dtype=torch.float32, device="cuda")
+
+    def call(**kw):
+        a = dict(out=out, q=dc.q, pool=dc.pool, block_table=dc.block_table, context_lens=dc.context_lens)
+        a.update(kw)
+        kvflow.kv_decode_attn(a["out"], a["q"], a["pool"], a["block_table"], a["context_lens"], dc.max_len,
+                              dc.scale, 0, ws)
+
+    call()                                                             # the well-formed call goes through
+    for bad in (dict(block_table=dc.block_table.long()), dict(context_lens=dc.context_lens.long()),
+                dict(q=dc.q.float()), dict(q=dc.q.transpose(0, 1)), dict(out=out[:, :, :32]),
+                dict(q=dc.q[:, :, :32].contiguous()), dict(block_table=dc.block_table[:2]),
+                dict(context_lens=dc.context_lens.cpu()), dict(out=out.to(torch.float16))):
+        with pytest.raises(ValueError):
+            call(**bad)
+    ids = torch.from_numpy(case.dirty_ids).cuda()
+    replica = torch.empty((len(case.dirty_ids),) + dc.pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+    kvflow.kv_pack_blocks(replica, dc.pool, ids)
+    with pytest.raises(ValueError):
+        kvflow.kv_pack_blocks(replica, dc.pool, ids.long())
+    with pytest.raises(ValueError):
+        kvflow.kv_pack_blocks(replica[:4], dc.pool, ids)                 # replica too small for the list
+    with pytest.raises(ValueError):
+        kvflow.kv_restore_blocks(dc.pool, replica, ids[::2])             # strided id list
+    torch.cuda.synchronize()
+
+
 def test_decode_batch_larger_than_one_launch_slice(oracle):
     """More sequences than one launch scans (4096): the call slices the batch; tiny contexts."""
     rng = np.random.default_rng(11)

@@ -213,3 +213,19 @@ def test_probe_rejects_bad_arguments_before_any_launch(lib):
     assert pr(mode=3) == -2 and pr(mode=-1) == -2 and pr(n=24) == -2
     assert pr(a=0) == -1 and pr(b=0) == -1 and pr(mode=0, b=0) == -1
     assert pr(a=0x20008) == -4 and pr(b=0x30004) == -4
+
+
+def test_binding_rejects_host_tensors_before_touching_the_library():
+    """The binding's own checks run on the host: a tensor that is not GPU memory never reaches a kernel."""
+    import torch
+    from paper_2601_22438_amd import kvflow
+    q = torch.zeros((2, 8, 64), dtype=torch.bfloat16)
+    pool = torch.zeros((8, 2, 2, 16, 64), dtype=torch.bfloat16)
+    table = torch.zeros((2, 4), dtype=torch.int32)
+    lens = torch.ones(2, dtype=torch.int32)
+    with pytest.raises(ValueError, match="GPU memory"):
+        kvflow.kv_decode_attn(torch.empty_like(q), q, pool, table, lens, 16, 0.125)
+    with pytest.raises(ValueError, match="GPU memory"):
+        kvflow.kv_pack_blocks(torch.empty_like(pool), pool, torch.zeros(8, dtype=torch.int32))
+    with pytest.raises(ValueError, match="GPU memory"):
+        kvflow.kv_restore_blocks(pool, torch.empty_like(pool), torch.zeros(8, dtype=torch.int32))
