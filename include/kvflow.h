@@ -128,6 +128,31 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * kv_decode_attn for callers that cannot allocate device memory and so have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments, preconditions and results (bit for bit) as kv_decode_attn; the
+ * workspace is a fixed array of KV_DECODE_STATIC_SCRATCH_BYTES inside the library's device code,
+ * one copy per GPU, held until the process ends.  The call allocates and frees nothing.
+ *   - Arguments whose kv_decode_workspace_bytes() exceeds KV_DECODE_STATIC_SCRATCH_BYTES are
+ *     refused with KV_ERR_WORKSPACE before any launch (at 8 query heads per KV head and head_dim
+ *     128 the array covers 256 workgroups and batch * num_kv_heads up to about 2900).
+ *   - The device that `stream` belongs to must be the current device of the calling thread.
+ *   - All calls on one GPU share that GPU's array: two calls that may overlap on the same GPU
+ *     (different streams without an ordering between them) race on it and give undefined
+ *     results.  Calls ordered by a stream or by events are fine; nothing has to be cleared
+ *     between them (the kernels never read what an earlier call left there).
+ *   - The first call on a device looks the array's address up (no allocation); make that call
+ *     outside graph capture.
+ * Errors: those of kv_decode_attn; WORKSPACE as above; LAUNCH also when the current device or
+ * the array's address cannot be obtained.
+ */
+#define KV_DECODE_STATIC_SCRATCH_BYTES (16u << 20)
+int kv_decode_attn_static(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
+                          const int32_t* block_table, int32_t max_blocks_per_seq,
+                          const int32_t* context_lens, int32_t batch, int32_t num_q_heads,
+                          int32_t max_context_len, float scale, int32_t num_workgroups, void* stream);
+
+/*
  * Recomputation of attention state over the paged cache (Sec. 3.2 item 3: a node that dropped
  * replicas under memory pressure recomputes them): causal attention of many query tokens per
  * sequence.  Sequence b has L = context_lens[b] tokens in the pool, the newest

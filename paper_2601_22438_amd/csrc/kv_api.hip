@@ -4,12 +4,40 @@
 #include "../../include/kvflow.h"
 #include "kv_internal.h"
 
+#include <atomic>
 #include <cmath>
 #include <vector>
 
 using namespace kvflow;
 
+// Decode workspace of kv_decode_attn_static: lives in every device's copy of the loaded code
+// object until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the per-device address it yields is what kernels and copies are given.
+// No kernel names the array, and it needs no `used` attribute: the host-side reference below is
+// what makes the compiler give the device symbol external linkage, which the runtime's lookup by
+// name requires (with the attribute the symbol stays internal and the lookup aborts).
+constexpr size_t kStaticScratchBytes = (size_t)KV_DECODE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// Device address of `scratch` per device ordinal, looked up once per device with that device
+// current.  Racing first calls look the same address up twice, which is harmless.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KV_ERR_LAUNCH;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return KV_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return KV_OK;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -165,6 +193,24 @@ int kv_decode_attn(void* out, int32_t out_dtype, const void* q, const kv_pool_de
         if (e != hipSuccess) return KV_ERR_LAUNCH;
     }
     return KV_OK;
+}
+
+int kv_decode_attn_static(void* out, int32_t out_dtype, const void* q, const kv_pool_desc* pool,
+                          const int32_t* block_table, int32_t max_blocks_per_seq,
+                          const int32_t* context_lens, int32_t batch, int32_t num_q_heads,
+                          int32_t max_context_len, float scale, int32_t num_workgroups, void* stream)
+{
+    // sizes beyond the fixed array are refused before anything else is looked at on the device
+    if (pool && batch > 0 && num_q_heads > 0) {
+        const size_t need = kv_decode_workspace_bytes(batch, num_q_heads, pool->num_kv_heads, pool->head_dim,
+                                                      max_context_len, num_workgroups);
+        if (need > kStaticScratchBytes) return KV_ERR_WORKSPACE;
+    }
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != KV_OK) return rc;
+    return kv_decode_attn(out, out_dtype, q, pool, block_table, max_blocks_per_seq, context_lens, batch,
+                          num_q_heads, max_context_len, scale, num_workgroups, ws, kStaticScratchBytes, stream);
 }
 
 int32_t kv_prefill_key_splits(int32_t batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t max_q_len,

@@ -54,6 +54,8 @@ def load() -> ctypes.CDLL:
     lib.kv_decode_workspace_bytes.argtypes = [I32, I32, I32, I32, I32, I32]
     lib.kv_decode_attn.restype = ctypes.c_int
     lib.kv_decode_attn.argtypes = [P, I32, P, PD, P, I32, P, I32, I32, I32, F, I32, P, SZ, P]
+    lib.kv_decode_attn_static.restype = ctypes.c_int
+    lib.kv_decode_attn_static.argtypes = [P, I32, P, PD, P, I32, P, I32, I32, I32, F, I32, P]
     lib.kv_prefill_attn.restype = ctypes.c_int
     lib.kv_prefill_attn.argtypes = [P, I32, P, PD, P, I32, P, P, I32, I32, I32, I64, F, I32, P, SZ, P]
     lib.kv_prefill_key_splits.restype = I32
@@ -219,6 +221,26 @@ def kv_decode_attn(out, q, pool, block_table, context_lens, max_context_len, sca
         _ptr(out), out_dtype, _ptr(q), ctypes.byref(pool_desc(pool)), _ptr(block_table),
         block_table.shape[1], _ptr(context_lens), batch, num_q_heads, int(max_context_len),
         float(scale), int(num_workgroups), _ptr(workspace), ws_bytes, _stream_handle(stream)))
+
+
+KV_DECODE_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def kv_decode_attn_static(out, q, pool, block_table, context_lens, max_context_len, scale,
+                          num_workgroups=0, stream=None) -> None:
+    """kv_decode_attn with the library's fixed per-GPU scratch array as workspace (allocates nothing)."""
+    _dev(q, "q", torch.bfloat16)
+    if q.dim() != 3 or q.shape[2] != _pool_data(pool).shape[4]:
+        raise ValueError("q must be bf16 [batch][num_q_heads][head_dim of the pool]")
+    batch, num_q_heads, _ = q.shape
+    _dev(out, "out", (torch.bfloat16, torch.float32), shape=q.shape)
+    _table(block_table, batch)
+    _dev(context_lens, "context_lens", torch.int32, shape=(batch,))
+    out_dtype = {torch.bfloat16: KV_DTYPE_BF16, torch.float32: KV_DTYPE_F32}[out.dtype]
+    _check(load().kv_decode_attn_static(
+        _ptr(out), out_dtype, _ptr(q), ctypes.byref(pool_desc(pool)), _ptr(block_table),
+        block_table.shape[1], _ptr(context_lens), batch, num_q_heads, int(max_context_len),
+        float(scale), int(num_workgroups), _stream_handle(stream)))
 
 
 def kv_prefill_key_splits(batch, num_q_heads, num_kv_heads, max_q_len, max_context_len) -> int:
