@@ -470,7 +470,8 @@ def bench_recompute(args, kvflow, W):
 
 
 def bench_yardsticks(args, kvflow, W):
-    """What plain streaming kernels reach on this device: the practical ceilings next to the 8 TB/s peak."""
+    """What plain streaming kernels reach on this device: the practical ceilings next to the 8 TB/s peak.
+    Three designs of each: the library's two probe kernels and torch's own fill / copy / sum-free read."""
     import torch
     nbytes = 4 << 30
     a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -478,9 +479,18 @@ def bench_yardsticks(args, kvflow, W):
     b.random_(0, 255)
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
     out = {"bytes": nbytes}
-    for name, fn, traffic in (("read_only", lambda: kvflow.kv_probe_stream(0, sink, b, nbytes), nbytes),
-                              ("write_only", lambda: kvflow.kv_probe_stream(1, a, None, nbytes), nbytes),
-                              ("contiguous_copy", lambda: kvflow.kv_probe_stream(2, a, b, nbytes), 2 * nbytes)):
+    a32, b32 = a.view(torch.int32), b.view(torch.int32)
+    runs = (
+        ("read_only", lambda: kvflow.kv_probe_stream(0, sink, b, nbytes), nbytes),
+        ("write_only", lambda: kvflow.kv_probe_stream(1, a, None, nbytes), nbytes),
+        ("contiguous_copy", lambda: kvflow.kv_probe_stream(2, a, b, nbytes), 2 * nbytes),
+        ("read_only_second_design", lambda: kvflow.kv_probe_stream(3, sink, b, nbytes), nbytes),
+        ("write_only_second_design", lambda: kvflow.kv_probe_stream(4, a, None, nbytes), nbytes),
+        ("contiguous_copy_second_design", lambda: kvflow.kv_probe_stream(5, a, b, nbytes), 2 * nbytes),
+        ("write_only_torch_fill", lambda: a32.fill_(7), nbytes),
+        ("contiguous_copy_torch", lambda: a32.copy_(b32), 2 * nbytes),
+    )
+    for name, fn, traffic in runs:
         d = time_calls(fn, 10, 3)
         gbps = traffic / (d["mean_ms"] * 1e-3) / 1e9
         out[name] = {**d, "traffic_GBps": gbps, "frac_hbm_peak": gbps / HBM_PEAK_GBPS}

@@ -319,6 +319,11 @@ int kv_validate_prefill(const kv_pool_desc* pool, const int32_t* block_table, in
  *   mode 0  read b once; a points at >= 16 writable bytes that are left untouched
  *   mode 1  write a once (contents unspecified)
  *   mode 2  a <- b, contiguous copy
+ *   mode 3, 4, 5  the same three with a second kernel design, so that a ceiling read off these
+ *           numbers does not rest on one kernel
+ * Modes 0-2 give every XCD a contiguous eighth of the buffer and write through at device scope
+ * (the design of the block-copy kernels; at most 32 GiB per call); modes 3-5 walk the buffer in
+ * workgroup order (a persistent grid for the read).
  * a, b: device pointers, 16-byte aligned, must not overlap.  Errors: SHAPE, NULL, ALIGN, LAUNCH.
  */
 int kv_probe_stream(int32_t mode, void* a, const void* b, size_t bytes, void* stream);

@@ -453,10 +453,12 @@ int kv_validate_block_ids(const kv_pool_desc* pool, const int32_t* block_ids, in
 
 int kv_probe_stream(int32_t mode, void* a, const void* b, size_t bytes, void* stream)
 {
-    if (mode < 0 || mode > 2 || bytes % 16) return KV_ERR_SHAPE;
+    if (mode < 0 || mode > 5 || bytes % 16) return KV_ERR_SHAPE;
     if (bytes == 0) return KV_OK;
-    if (!a || (mode != 1 && !b)) return KV_ERR_NULL;
-    if (!aligned16(a) || (mode != 1 && !aligned16(b))) return KV_ERR_ALIGN;
+    const int kind = mode % 3;
+    if (!a || (kind != 1 && !b)) return KV_ERR_NULL;
+    if (!aligned16(a) || (kind != 1 && !aligned16(b))) return KV_ERR_ALIGN;
+    if (mode <= 2 && bytes > ((size_t)32 << 30)) return KV_ERR_SHAPE;
     return launch_probe(mode, a, b, bytes, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }
 

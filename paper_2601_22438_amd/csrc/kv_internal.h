@@ -97,7 +97,7 @@ hipError_t launch_gather_tokens(const void* pool, void* k_out, void* v_out, cons
 hipError_t launch_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* ids_out, int64_t capacity,
                                 int32_t* count_out, int clear, hipStream_t stream);
 
-// mode 0: read b (a = 4 writable bytes), 1: fill a, 2: a <- b; bytes is a multiple of 16
+// mode 0 / 3: read b (a = 16 writable bytes), 1 / 4: fill a, 2 / 5: a <- b; bytes is a multiple of 16
 hipError_t launch_probe(int mode, void* a, const void* b, size_t bytes, hipStream_t stream);
 
 }  // namespace kvflow

@@ -1,6 +1,10 @@
 // Yardsticks for the roofline tables: what plain streaming kernels (read only, write only, contiguous
 // copy) reach on the device at hand, with the same access style as the product kernels (16-byte
 // accesses, non-temporal policy).  Diagnostics only; nothing else in the library uses them.
+// Two designs of each, so that a ceiling does not rest on one kernel: modes 0-2 deal the buffer to
+// the XCDs in contiguous eighths, one 16 KiB workgroup per piece, stores written through at device
+// scope (the design of the block-copy kernels); modes 3-5 walk the buffer in workgroup order with
+// plain non-temporal accesses (a persistent grid for the read).
 
 #include "kv_internal.h"
 
@@ -61,6 +65,38 @@ __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(u32x4* __rest
     }
 }
 
+// ---- modes 0-2: XCD x = blockIdx % 8 owns chunks [x * per, (x + 1) * per) of 16 KiB
+constexpr int kXThreads = 1024;
+constexpr int kXcds = 8;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t span_rsrc(const void* base, size_t first_vec, size_t n)
+{
+    // the 16 KiB chunk starting at vector first_vec, cut off at the end of the buffer
+    const size_t left = (n - first_vec) * 16;
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + first_vec * 16), 0,
+                                             (int)(left < (size_t)kXThreads * 16 ? left : (size_t)kXThreads * 16), 0x00020000);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kXThreads) void probe_xcd_kernel(u32x4* __restrict__ a, const u32x4* __restrict__ b,
+                                                               size_t n, size_t per)
+{
+    const size_t x = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
+    const size_t first = (x * per + k) * kXThreads;
+    if (k >= per || first >= n) return;
+    const uint32_t off = threadIdx.x * 16;
+    if (MODE == 0) {
+        const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(span_rsrc(b, first, n), off, 0, 2);   // out of range reads 0
+        if (r.x == 0x9E3779B9u && r.y == 0x7F4A7C15u && r.z == 0xF39CC060u && r.w == 0x5CEDC834u) a[0] = r;
+    } else if (MODE == 1) {
+        const u32x4 val = {blockIdx.x, threadIdx.x, 0u, 0u};
+        __builtin_amdgcn_raw_buffer_store_b128(val, span_rsrc(a, first, n), off, 0, 2 | 16);
+    } else {
+        const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(span_rsrc(b, first, n), off, 0, 2);
+        __builtin_amdgcn_raw_buffer_store_b128(r, span_rsrc(a, first, n), off, 0, 2 | 16);
+    }
+}
+
 hipError_t launch_probe(int mode, void* a, const void* b, size_t bytes, hipStream_t stream)
 {
     const size_t n = bytes / 16;
@@ -68,6 +104,16 @@ hipError_t launch_probe(int mode, void* a, const void* b, size_t bytes, hipStrea
     const size_t groups = (n + per_group - 1) / per_group;
     if (groups > 0x7FFFFFFFu) return hipErrorInvalidValue;
     const dim3 block(kProbeThreads);
+    if (mode <= 2) {
+        const size_t chunks = (n + kXThreads - 1) / kXThreads, per = (chunks + kXcds - 1) / kXcds;
+        if (per * kXcds > (1u << 21)) return hipErrorInvalidValue;         // gridDim.x * blockDim.x stays below 2^32
+        const dim3 grid((uint32_t)(per * kXcds)), blk(kXThreads);
+        if (mode == 0) hipLaunchKernelGGL(probe_xcd_kernel<0>, grid, blk, 0, stream, (u32x4*)a, (const u32x4*)b, n, per);
+        else if (mode == 1) hipLaunchKernelGGL(probe_xcd_kernel<1>, grid, blk, 0, stream, (u32x4*)a, (const u32x4*)b, n, per);
+        else hipLaunchKernelGGL(probe_xcd_kernel<2>, grid, blk, 0, stream, (u32x4*)a, (const u32x4*)b, n, per);
+        return hipGetLastError();
+    }
+    mode -= 3;
     if (mode == 0)
         hipLaunchKernelGGL(probe_read_kernel, dim3(kReadGroups), block, 0, stream, (const u32x4*)b, n, (u32x4*)a);
     else if (mode == 1)

@@ -296,16 +296,23 @@ def test_decode_large_scores_and_rising_maximum(oracle):
         assert_close_to_oracle(dc.decode(torch.float32, workgroups=wgs), want, f"rising max workgroups={wgs}")
 
 
-def test_streaming_probes_copy_exactly_and_leave_the_sink_alone():
+@pytest.mark.parametrize("design", [0, 3])
+def test_streaming_probes_copy_exactly_and_leave_the_sink_alone(design):
     n = (1 << 22) + 16 * 37                                         # not a multiple of the kernels' stride
     src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
     dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
-    kvflow.kv_probe_stream(2, dst, src, n)
+    kvflow.kv_probe_stream(design + 2, dst, src, n)
     sink = torch.full((16,), 7, dtype=torch.uint8, device="cuda")
-    kvflow.kv_probe_stream(0, sink, src, n)
+    kvflow.kv_probe_stream(design, sink, src, n)
     torch.cuda.synchronize()
     assert torch.equal(dst[:n], src) and torch.all(dst[n:] == 0)
     assert torch.all(sink == 7)
-    kvflow.kv_probe_stream(1, dst, None, n)                         # contents unspecified, bounds are not
+    kvflow.kv_probe_stream(design + 1, dst, None, n)                # contents unspecified, bounds are not
     torch.cuda.synchronize()
     assert torch.all(dst[n:] == 0)
+    # a buffer shorter than one XCD's share, and one of a single vector
+    for m in (16, 16 * 5, 16 * 1024 * 3 + 16):
+        small = torch.zeros(m + 32, dtype=torch.uint8, device="cuda")
+        kvflow.kv_probe_stream(design + 2, small, src, m)
+        torch.cuda.synchronize()
+        assert torch.equal(small[:m], src[:m]) and torch.all(small[m:] == 0)

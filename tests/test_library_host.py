@@ -210,8 +210,9 @@ def test_append_packed_rejects_bad_arguments_before_any_launch(lib):
 def test_probe_rejects_bad_arguments_before_any_launch(lib):
     pr = lambda mode=2, a=0x20000, b=0x30000, n=1 << 20: lib.kv_probe_stream(mode, a, b, n, None)
     assert pr(n=0) == 0
-    assert pr(mode=3) == -2 and pr(mode=-1) == -2 and pr(n=24) == -2
-    assert pr(a=0) == -1 and pr(b=0) == -1 and pr(mode=0, b=0) == -1
+    assert pr(mode=6) == -2 and pr(mode=-1) == -2 and pr(n=24) == -2
+    assert pr(n=(32 << 30) + 16) == -2 and pr(mode=5, a=0, n=(32 << 30) + 16) == -1
+    assert pr(a=0) == -1 and pr(b=0) == -1 and pr(mode=0, b=0) == -1 and pr(mode=3, b=0) == -1 and pr(mode=4, a=0) == -1
     assert pr(a=0x20008) == -4 and pr(b=0x30004) == -4
 
 
