@@ -36,5 +36,31 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def kernel_resources(source: str) -> dict:
+    """Compile one HIP source for the device only and return, per kernel, the registers and scratch bytes the
+    compiler reports ({mangled name: {"vgprs": n, "scratch": bytes per lane, "spills": n}})."""
+    import re
+    import tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [HIPCC, *[f for f in FLAGS if f not in ("-shared", "-fPIC")], "--cuda-device-only", "-c",
+               os.path.join(CSRC, source), "-o", os.path.join(tmp, "dev.o"), "-Rpass-analysis=kernel-resource-usage"]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    out, name = {}, None
+    for line in res.stdout.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            out[name] = {}
+            continue
+        for key, pat in (("vgprs", r" VGPRs: (\d+)"), ("scratch", r"ScratchSize \[bytes/lane\]: (\d+)"),
+                         ("spills", r"VGPRs Spill: (\d+)")):
+            m = re.search(pat, line)
+            if m and name is not None:
+                out[name][key] = int(m.group(1))
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose="-v" in sys.argv))

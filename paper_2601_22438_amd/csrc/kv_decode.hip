@@ -65,53 +65,14 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
     const int g = lane >> 4, j = lane & 15;
     const int B = p.batch, Hkv = p.num_kv_heads, G = p.group;
 
-    // ---- start-up: cum[b] = number of tiles of sequences before b (exclusive scan in LDS)
+    // ---- start-up: tile counts of the sequences (scan in LDS), this wavefront's run, its first tile
     int* cum = (int*)smem;                                            // [B + 1]
-    {
-        __shared__ int wave_tot[kDecodeWaves];
-        const int per = (B + kDecodeThreads - 1) / kDecodeThreads;
-        const int lo = min(B, (int)threadIdx.x * per), hi = min(B, lo + per);
-        int mine = 0;
-        for (int b = lo; b < hi; ++b) mine += (lens_ptr[b] + kTileTokens - 1) / kTileTokens;
-        int incl = mine;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int t = __shfl_up(incl, off);
-            if (lane >= off) incl += t;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        int before = incl - mine;
-        for (int w = 0; w < wave; ++w) before += wave_tot[w];
-        for (int b = lo; b < hi; ++b) {
-            cum[b] = before;
-            before += (lens_ptr[b] + kTileTokens - 1) / kTileTokens;
-        }
-        if (threadIdx.x == kDecodeThreads - 1) cum[B] = before;       // its range ends at B
-        __syncthreads();
-        if (blockIdx.x == 0)                                          // the merge kernel reads this copy
-            for (int b = threadIdx.x; b <= B; b += kDecodeThreads) ws_cum[b] = cum[b];
-    }
-    const int T = Hkv * cum[B];
-    const int W = gridDim.x * kDecodeWaves;
-    const int base = T / W, rem = T % W;
-    const int w = blockIdx.x * kDecodeWaves + wave;
-    const int t_begin = run_start(w, base, rem), t_end = run_start(w + 1, base, rem);
-
-    // ---- locate the first tile of this run: last b with Hkv * cum[b] <= t_begin
+    const RunSpan rs = split_into_runs<kTileTokens>(cum, ws_cum, lens_ptr, B, Hkv, lane, wave);
+    const int t_begin = rs.t_begin, t_end = rs.t_end;
     TileDesc cur = {0, 0, 0, 0, 0, 0, 0};
     if (t_begin < t_end) {
-        int lo = 0, hi = B;                                           // Hkv*cum[lo] <= t_begin < Hkv*cum[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (Hkv * cum[mid] <= t_begin) lo = mid; else hi = mid;
-        }
-        cur.b = lo;
-        cur.ntiles = cum[lo + 1] - cum[lo];
-        const int r = t_begin - Hkv * cum[lo];
-        cur.kvh = r / cur.ntiles;
-        cur.tile = r % cur.ntiles;
-        cur.L = lens_ptr[lo];
+        const TilePos pos = locate_tile(cum, lens_ptr, B, Hkv, t_begin);
+        cur.b = pos.b; cur.kvh = pos.kvh; cur.tile = pos.tile; cur.L = pos.L; cur.ntiles = pos.ntiles;
     }
     __syncthreads();                                                  // cum[] is dead; LDS becomes V staging
     if (t_begin >= t_end) return;
@@ -301,16 +262,7 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
 
         // ---- leaving the row: one record per query head, then start afresh
         if (row_ends) {
-            float l_tot = l_run + __shfl_xor(l_run, 16);
-            l_tot += __shfl_xor(l_tot, 32);
-            if (j < G) {
-                const int64_t slot = (int64_t)w + (int64_t)cur.b * Hkv + cur.kvh;
-                float* rec = ws_records + (slot * G + j) * S::kRecord;
-#pragma unroll
-                for (int dt = 0; dt < S::kDTiles; ++dt)
-                    *(f32x4*)(rec + 16 * dt + 4 * g) = oacc[dt];      // channels 16dt + 4g .. +3
-                if (g == 0) { rec[D] = m_run; rec[D + 1] = l_tot; }
-            }
+            leave_row<D>(ws_records, oacc, m_run, l_run, rs.w, cur.b, cur.kvh, Hkv, G, g, j);
             m_run = -INFINITY;
             l_run = 0.f;
 #pragma unroll

@@ -1,5 +1,6 @@
 // Pieces shared by the decode kernels (bf16 pool and FP8 pool): vector types, the split of the
-// flat tile space into runs, and the kernel that merges the per-run records.
+// flat tile space into runs, the record a run leaves when it leaves a (sequence, KV head) row,
+// and the kernel that merges the records of a row.
 #pragma once
 
 #include "kv_internal.h"
@@ -36,6 +37,97 @@ __device__ __forceinline__ int run_of_tile(int t, int base, int rem)
 {
     const int big = rem * (base + 1);                // tiles held by the runs that got one extra
     return t < big ? t / (base + 1) : rem + (t - big) / base;
+}
+
+// The run of one wavefront: flat tiles [t_begin, t_end) of the T tiles dealt to W runs.
+struct RunSpan {
+    int w, W, base, rem, t_begin, t_end;
+};
+
+// Where a flat tile lies: sequence, KV head, tile within the sequence, and the sequence's size.
+struct TilePos {
+    int b, kvh, tile, ntiles, L;
+};
+
+// Start-up of a decode workgroup (all kDecodeThreads threads call it): cum[b] = number of
+// kTile-token tiles of the sequences before b (exclusive scan of the context lengths in LDS,
+// cum has batch + 1 entries; workgroup 0 also copies it to ws_cum for the merge kernel), then
+// this wavefront's run.  cum[] is complete on return.
+template <int kTile>
+__device__ __forceinline__ RunSpan split_into_runs(int* cum, int32_t* __restrict__ ws_cum,
+                                                   const int32_t* __restrict__ lens_ptr, int B, int Hkv, int lane,
+                                                   int wave)
+{
+    __shared__ int wave_tot[kDecodeWaves];
+    const int per = (B + kDecodeThreads - 1) / kDecodeThreads;
+    const int lo = min(B, (int)threadIdx.x * per), hi = min(B, lo + per);
+    int mine = 0;
+    for (int b = lo; b < hi; ++b) mine += (lens_ptr[b] + kTile - 1) / kTile;
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int before = incl - mine;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    for (int b = lo; b < hi; ++b) {
+        cum[b] = before;
+        before += (lens_ptr[b] + kTile - 1) / kTile;
+    }
+    if (threadIdx.x == kDecodeThreads - 1) cum[B] = before;           // its range ends at B
+    __syncthreads();
+    if (blockIdx.x == 0)                                              // the merge kernel reads this copy
+        for (int b = threadIdx.x; b <= B; b += kDecodeThreads) ws_cum[b] = cum[b];
+    RunSpan rs;
+    const int T = Hkv * cum[B];
+    rs.W = gridDim.x * kDecodeWaves;
+    rs.base = T / rs.W;
+    rs.rem = T % rs.W;
+    rs.w = blockIdx.x * kDecodeWaves + wave;
+    rs.t_begin = run_start(rs.w, rs.base, rs.rem);
+    rs.t_end = run_start(rs.w + 1, rs.base, rs.rem);
+    return rs;
+}
+
+// Position of flat tile t (which must exist): the last b with Hkv * cum[b] <= t.
+__device__ __forceinline__ TilePos locate_tile(const int* cum, const int32_t* __restrict__ lens_ptr, int B, int Hkv, int t)
+{
+    int lo = 0, hi = B;                                               // Hkv*cum[lo] <= t < Hkv*cum[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (Hkv * cum[mid] <= t) lo = mid; else hi = mid;
+    }
+    TilePos pos;
+    pos.b = lo;
+    pos.ntiles = cum[lo + 1] - cum[lo];
+    const int r = t - Hkv * cum[lo];
+    pos.kvh = r / pos.ntiles;
+    pos.tile = r % pos.ntiles;
+    pos.L = lens_ptr[lo];
+    return pos;
+}
+
+// The run leaves row (b, kvh).  Lane (g, j) holds, for query head j of the group (j < G), the
+// un-normalised output channels 16dt + 4g .. +3 in oacc[dt], the head's reference maximum m_run
+// and its share l_run of the denominator.  One record per query head (O, m, l) goes to slot
+// run + row index, unique because both grow along the flat space.
+template <int D>
+__device__ __forceinline__ void leave_row(float* __restrict__ ws_records, const f32x4 (&oacc)[D / 16], float m_run,
+                                          float l_run, int run, int b, int kvh, int Hkv, int G, int g, int j)
+{
+    constexpr int kRecord = D + kRecordPad;
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (j < G) {
+        const int64_t slot = (int64_t)run + (int64_t)b * Hkv + kvh;
+        float* rec = ws_records + (slot * G + j) * kRecord;
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) *(f32x4*)(rec + 16 * dt + 4 * g) = oacc[dt];  // channels 16dt + 4g .. +3
+        if (g == 0) { rec[D] = m_run; rec[D + 1] = l_tot; }
+    }
 }
 
 // Combines the records of one (sequence, query head) in a fixed order and normalises.

@@ -230,3 +230,16 @@ def test_binding_rejects_host_tensors_before_touching_the_library():
         kvflow.kv_pack_blocks(torch.empty_like(pool), pool, torch.zeros(8, dtype=torch.int32))
     with pytest.raises(ValueError, match="GPU memory"):
         kvflow.kv_restore_blocks(pool, torch.empty_like(pool), torch.zeros(8, dtype=torch.int32))
+
+
+def test_decode_kernels_need_no_scratch_memory():
+    """A decode kernel that spills registers or calls a function with a stack frame makes every dispatch
+    reserve scratch memory, which costs tens of microseconds per call on this device: keep them at zero."""
+    from paper_2601_22438_amd.build import kernel_resources
+    seen = 0
+    for source in ("kv_decode.hip", "kv_decode_fp8.hip"):
+        for name, use in kernel_resources(source).items():
+            if "decode_partition" in name:
+                seen += 1
+                assert use["scratch"] == 0 and use["spills"] == 0, (name, use)
+    assert seen == 4
