@@ -300,15 +300,16 @@ def bench_replication_mix(args, kvflow, W):
         t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0.record(main)
         for _ in range(n_iter):
-            if with_pack == "side":
+            if with_pack in ("side", "fork_only"):
                 ev = torch.cuda.Event()
                 ev.record(main)
                 side.wait_event(ev)
-                kvflow.kv_pack_blocks(replica, pool, ids, stream=side)
+                if with_pack == "side":
+                    kvflow.kv_pack_blocks(replica, pool, ids, stream=side)
             dec.run()
             if with_pack == "same":
                 kvflow.kv_pack_blocks(replica, pool, ids)
-        if with_pack == "side":
+        if with_pack in ("side", "fork_only"):
             done = torch.cuda.Event()
             done.record(side)
             main.wait_event(done)
@@ -320,9 +321,57 @@ def bench_replication_mix(args, kvflow, W):
     alone_ms = min(train(30, None) for _ in range(3))
     both_ms = min(train(30, "side") for _ in range(3))
     same_ms = min(train(30, "same") for _ in range(3))
+    fork_ms = min(train(30, "fork_only") for _ in range(3))
     o = {"ms_per_step_decode_only": alone_ms, "ms_per_step_with_pack_on_side_stream": both_ms,
          "ms_per_step_with_pack_on_same_stream": same_ms,
-         "note": "the side-stream figure includes one event record/wait per step between the two streams"}
+         "ms_per_step_with_the_fork_event_but_no_pack": fork_ms,
+         "note": "eager launches; the side-stream figure includes one event record/wait per step between the two "
+                 "streams, whose cost alone is the fork-event figure (it is paid once per fork, here once per "
+                 "150 us decode call; a serving step forks once per token step of all layers)"}
+
+    # The same three trains captured once into HIP graphs: the fork and join between the streams become graph
+    # dependencies, so a replay makes no host-side event call.  `steps` steps per graph.
+    def graph_train(with_pack, steps=20):
+        cap, side2 = torch.cuda.Stream(), torch.cuda.Stream()
+        cap.wait_stream(main)
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(cap):
+            with torch.cuda.graph(gr, stream=cap):
+                for _ in range(steps):
+                    if with_pack == "side":
+                        side2.wait_stream(cap)
+                        kvflow.kv_pack_blocks(replica, pool, ids, stream=side2)
+                    dec.run(stream=cap)
+                    if with_pack == "same":
+                        kvflow.kv_pack_blocks(replica, pool, ids, stream=cap)
+                    if with_pack == "side":
+                        cap.wait_stream(side2)
+        torch.cuda.synchronize()
+        gr.replay()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(5):
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0.record(main)
+            gr.replay()
+            t1.record(main)
+            torch.cuda.synchronize()
+            ms = t0.elapsed_time(t1) / steps
+            best = ms if best is None else min(best, ms)
+        return best
+
+    graphs = None
+    try:
+        g_alone, g_side, g_same = graph_train(None), graph_train("side"), graph_train("same")
+        graphs = {"ms_per_step_decode_only": g_alone, "ms_per_step_with_pack_on_side_stream": g_side,
+                  "ms_per_step_with_pack_on_same_stream": g_same,
+                  "side_stream_slowdown_pct": 100.0 * (g_side / g_alone - 1.0),
+                  "same_stream_slowdown_pct": 100.0 * (g_same / g_alone - 1.0),
+                  "added_traffic_pct": 100.0 * 2 * n * g.block_bytes / case.kv_bytes,
+                  "note": "20 steps per graph; decode is bound by HBM bandwidth, so the pack's own read+write traffic "
+                          "(added_traffic_pct of the decode's) is the floor of any slowdown"}
+    except Exception as exc:                                  # capture across two streams is a convenience figure
+        log(f"[bench] two-stream graph skipped: {exc}")
     # the on-device replication loop of one step: append the new tokens, collect the dirty list, pack it
     rs = np.random.SeedSequence(4242).spawn(2)
     k_new = bf16_dev(W.normal_bf16(rs[0], (case.batch, g.num_kv_heads, g.head_dim)))
@@ -399,8 +448,11 @@ def bench_replication_mix(args, kvflow, W):
                          "frac_hbm_peak": kv / (d["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "pack_alone": {**p, **copy_rates(n * g.block_bytes, p["mean_ms"])},
         "back_to_back_steps": o,
+        "back_to_back_steps_replayed_from_hip_graphs": graphs,
         "decode_slowdown_pct": 100.0 * (both_ms / alone_ms - 1.0),
         "same_stream_slowdown_pct": 100.0 * (same_ms / alone_ms - 1.0),
+        "fork_event_alone_slowdown_pct": 100.0 * (fork_ms / alone_ms - 1.0),
+        "added_traffic_floor_pct": 100.0 * 2 * n * g.block_bytes / case.kv_bytes,
     }
 
 

@@ -101,3 +101,44 @@ def test_recompute_call_captured_in_a_graph(oracle, key_splits):
     call()
     torch.cuda.synchronize()
     assert torch.equal(out, replayed)
+
+
+def test_two_stream_step_captured_in_a_graph(oracle):
+    """The replication step as a graph: fork -> {decode on the capture stream, pack on a second stream} ->
+    join, three steps per graph.  The cross-stream edges are graph dependencies (no host-side event calls at
+    replay); every replay gives the decode output of decode alone, bit for bit, and the oracle's replica."""
+    case = W.replication_mix(shrink=8, batch=32)
+    g = case.geom
+    dc = DeviceCase(case)
+    alone = dc.decode(torch.bfloat16)
+    ids = torch.from_numpy(case.dirty_ids).cuda()
+    replica = torch.zeros((len(case.dirty_ids),) + dc.pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros_like(alone)
+    nbytes = kvflow.kv_decode_workspace_bytes(case.batch, g.num_q_heads, g.num_kv_heads, g.head_dim, dc.max_len)
+    ws = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")
+    want_replica = oracle.pack_blocks(case.pool, case.dirty_ids)
+    # warm both kernels outside the capture
+    kvflow.kv_decode_attn(out, dc.q, dc.pool, dc.block_table, dc.context_lens, dc.max_len, dc.scale, 0, ws)
+    kvflow.kv_pack_blocks(replica, dc.pool, ids)
+    torch.cuda.synchronize()
+    cap, side = torch.cuda.Stream(), torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            for _ in range(3):
+                side.wait_stream(cap)                                   # fork
+                kvflow.kv_pack_blocks(replica, dc.pool, ids, stream=side)
+                kvflow.kv_decode_attn(out, dc.q, dc.pool, dc.block_table, dc.context_lens, dc.max_len, dc.scale,
+                                      0, ws, stream=cap)
+                cap.wait_stream(side)                                   # join
+    torch.cuda.synchronize()
+    for i in range(4):
+        out.zero_(); replica.zero_(); ws.fill_(float("nan"))           # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, alone), f"replay {i}: decode beside pack differs from decode alone"
+        assert np.array_equal(bits_of(replica), want_replica), f"replay {i}: replica differs from the oracle's"
+    assert_close_to_oracle(out, oracle.decode_attn(case.q, case.pool, case.block_table, case.context_lens, g.scale),
+                           "two-stream graph")
