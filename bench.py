@@ -430,11 +430,22 @@ def bench_replication_mix(args, kvflow, W):
         with torch.cuda.stream(side):
             host_replica.copy_(dev_staging, non_blocking=True)       # DMA engine, not the compute units
 
-    host = {"blocks": n_host, "payload_MB": host_payload / 1e6, "decode_steps": 40}
+    chunk_blocks = max(1, (32 << 20) // g.block_bytes)                  # two staging halves of 32 MiB
+    small_staging = torch.empty((2 * chunk_blocks,) + pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+    copy_stream = torch.cuda.Stream()
+
+    def double_buffered():
+        copy_stream.wait_stream(side)
+        kvflow.kv_pack_blocks_staged(host_replica, pool, host_ids, small_staging, chunk_blocks, side, copy_stream)
+        side.wait_stream(copy_stream)                                   # the side-stream timer closes after the last copy
+
+    host = {"blocks": n_host, "payload_MB": host_payload / 1e6, "decode_steps": 40,
+            "double_buffer_staging_MB": 2 * chunk_blocks * g.block_bytes / 1e6}
     decode_steps_beside(None)
     base_med, base_sum, _ = decode_steps_beside(None)
     host["decode_alone"] = {"median_step_ms": base_med, "total_ms": base_sum}
-    for label, fn in (("pack_kernel_writes_host_memory", direct), ("pack_to_device_staging_then_dma", staged)):
+    for label, fn in (("pack_kernel_writes_host_memory", direct), ("pack_to_device_staging_then_dma", staged),
+                      ("pack_staged_double_buffered", double_buffered)):
         decode_steps_beside(fn)
         med, tot, side_ms = decode_steps_beside(fn)
         host[label] = {"transfer_ms": side_ms, "payload_GBps": host_payload / (side_ms * 1e-3) / 1e9,

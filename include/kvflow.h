@@ -287,6 +287,30 @@ int kv_collect_dirty(uint32_t* dirty_bitmap, int64_t num_blocks, int32_t* dirty_
                      int32_t* dirty_count, int32_t clear, void* stream);
 
 /*
+ * kv_pack_blocks into a destination on the far side of a slow link (pinned host memory standing in
+ * for a peer's buffer; Sec. 3.2 item 3: replication proceeds block by block in the background,
+ * Sec. 3.3: over the network), through a small double-buffered device staging area:
+ *     dst[i] <- pool[block_ids[i]]   for i in [0, n), list order, as kv_pack_blocks.
+ * The list is cut into chunks of chunk_blocks blocks.  Chunk c is packed at HBM speed into half
+ * c % 2 of `staging` on pack_stream and then copied to dst by the copy engine on copy_stream, so
+ * that the pack of chunk c + 1 runs beside the copy of chunk c and the compute units are busy with
+ * replication only for the short pack kernels.  The ordering between the two streams (half
+ * packed -> copy may start; copy done -> half may be packed again) is enqueued with events that
+ * the call creates and releases itself; the call does not wait for anything.
+ *   dst           n * kv_block_bytes() bytes, 16-byte aligned: pinned host memory, or device
+ *                 memory the copy engine can reach; written
+ *   staging       device, 2 * chunk_blocks * kv_block_bytes() bytes, 16-byte aligned; scratch
+ *   chunk_blocks  > 0; blocks per chunk (e.g. 32 MiB worth)
+ *   pack_stream, copy_stream   two streams of the caller (they may be the same stream, which
+ *                 serialises packs and copies); the transfer is complete when copy_stream has passed
+ *                 the enqueued work, and staging may be reused when both streams have
+ * Preconditions as for kv_pack_blocks.  Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, LAUNCH (also when
+ * an event cannot be created or a copy cannot be enqueued).  n == 0 returns KV_OK with nothing enqueued.
+ */
+int kv_pack_blocks_staged(void* dst, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n, void* staging,
+                          int64_t chunk_blocks, void* pack_stream, void* copy_stream);
+
+/*
  * kv_pack_blocks with the list length taken from device memory, so that the loop
  * append -> collect -> pack runs without the host seeing the list:
  *     replica[i] <- pool[block_ids[i]]   for i in [0, min(*count, max_n)).

@@ -313,6 +313,45 @@ int kv_pack_blocks_counted(void* replica, const kv_pool_desc* pool, const int32_
     return copy_blocks(replica, pool, block_ids, max_n, count, true, stream);
 }
 
+int kv_pack_blocks_staged(void* dst, const kv_pool_desc* pool, const int32_t* block_ids, int64_t n, void* staging,
+                          int64_t chunk_blocks, void* pack_stream, void* copy_stream)
+{
+    int rc = check_pool(pool);
+    if (rc != KV_OK) return rc;
+    if (n < 0 || chunk_blocks <= 0) return KV_ERR_SHAPE;
+    if (n == 0) return KV_OK;
+    if (!dst || !block_ids || !staging) return KV_ERR_NULL;
+    if (!aligned16(dst) || !aligned16(staging)) return KV_ERR_ALIGN;
+    const size_t bb = block_bytes_of(pool);
+    const size_t chunk_bytes = (size_t)chunk_blocks * bb;
+    hipStream_t ps = (hipStream_t)pack_stream, cs = (hipStream_t)copy_stream;
+    // packed[k]: staging half k holds a packed chunk; copied[k]: its copy has left the half
+    hipEvent_t packed[2] = {nullptr, nullptr}, copied[2] = {nullptr, nullptr};
+    for (int k = 0; k < 2; ++k)
+        if (hipEventCreateWithFlags(&packed[k], hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&copied[k], hipEventDisableTiming) != hipSuccess)
+            rc = KV_ERR_LAUNCH;
+    int64_t chunk = 0;
+    for (int64_t first = 0; rc == KV_OK && first < n; first += chunk_blocks, ++chunk) {
+        const int k = (int)(chunk & 1);
+        const int64_t nb = n - first < chunk_blocks ? n - first : chunk_blocks;
+        char* half = (char*)staging + (size_t)k * chunk_bytes;
+        if (chunk >= 2 && hipStreamWaitEvent(ps, copied[k], 0) != hipSuccess) { rc = KV_ERR_LAUNCH; break; }
+        rc = copy_blocks(half, pool, block_ids + first, nb, nullptr, true, ps);
+        if (rc != KV_OK) break;
+        if (hipEventRecord(packed[k], ps) != hipSuccess || hipStreamWaitEvent(cs, packed[k], 0) != hipSuccess ||
+            hipMemcpyAsync((char*)dst + (size_t)first * bb, half, (size_t)nb * bb, hipMemcpyDefault, cs) != hipSuccess ||
+            hipEventRecord(copied[k], cs) != hipSuccess)
+            rc = KV_ERR_LAUNCH;
+    }
+    // an event may be destroyed while work that uses it is still in flight: the runtime keeps it until then
+    for (int k = 0; k < 2; ++k) {
+        if (packed[k]) (void)hipEventDestroy(packed[k]);
+        if (copied[k]) (void)hipEventDestroy(copied[k]);
+    }
+    return rc;
+}
+
 int kv_append_tokens(const kv_pool_desc* pool, const void* k_new, const void* v_new,
                      const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* positions,
                      int32_t batch, uint32_t* dirty_bitmap, void* stream)

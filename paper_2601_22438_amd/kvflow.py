@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.kv_pack_blocks.argtypes = [P, PD, P, I64, P]
     lib.kv_restore_blocks.restype = ctypes.c_int
     lib.kv_restore_blocks.argtypes = [PD, P, P, I64, P]
+    lib.kv_pack_blocks_staged.restype = ctypes.c_int
+    lib.kv_pack_blocks_staged.argtypes = [P, PD, P, I64, P, I64, P, P]
     lib.kv_pack_blocks_counted.restype = ctypes.c_int
     lib.kv_pack_blocks_counted.argtypes = [P, PD, P, P, I64, P]
     lib.kv_append_tokens.restype = ctypes.c_int
@@ -291,6 +293,17 @@ def kv_restore_blocks(pool, replica, block_ids, n=None, stream=None) -> None:
     _replica(replica, pool, n)
     _check(load().kv_restore_blocks(ctypes.byref(pool_desc(pool)), _ptr(replica), _ptr(block_ids), n,
                                     _stream_handle(stream)))
+
+
+def kv_pack_blocks_staged(dst, pool, block_ids, staging, chunk_blocks, pack_stream, copy_stream, n=None) -> None:
+    """Enqueue dst[i] <- pool[block_ids[i]] through the double-buffered device staging area: packs on
+    pack_stream, copies of the packed chunks to dst (pinned host memory or a peer's buffer) on copy_stream."""
+    n = block_ids.numel() if n is None else int(n)
+    _dev(block_ids, "block_ids", torch.int32, numel=n)
+    _replica(dst, pool, n, "dst")
+    _replica(_dev(staging, "staging"), pool, 2 * int(chunk_blocks), "staging")
+    _check(load().kv_pack_blocks_staged(_ptr(dst), ctypes.byref(pool_desc(pool)), _ptr(block_ids), n, _ptr(staging),
+                                        int(chunk_blocks), _stream_handle(pack_stream), _stream_handle(copy_stream)))
 
 
 def kv_pack_blocks_counted(replica, pool, block_ids, count, max_n=None, stream=None) -> None:

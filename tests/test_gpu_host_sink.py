@@ -74,3 +74,53 @@ def test_decode_is_unchanged_while_packing_to_host_on_a_side_stream(oracle):
     torch.cuda.synchronize()
     assert torch.equal(out, alone)
     assert np.array_equal(host_bits(replica), oracle.pack_blocks(case.pool, case.in_use_ids[:512]))
+
+
+@pytest.mark.parametrize("n_list,chunk", [(4096, 512), (1000, 300), (7, 16), (5, 1), (0, 8)])
+def test_double_buffered_staged_transfer_matches_oracle(oracle, n_list, chunk):
+    """kv_pack_blocks_staged: the list goes to pinned host memory through two staging halves of `chunk`
+    blocks each (4096 blocks of 64 KiB = 268 MB through 2 x 32 MiB in the first case; ragged last
+    chunks, a list shorter than one chunk, one block per chunk and the empty list in the others)."""
+    g = W.Geometry(32, 8, 128, 16)
+    lens = np.full(8, 8192, np.int32)                                   # 4096 in-use blocks of 64 KiB
+    case = W.make_decode_case("t", 307, g, lens, dirty="last")
+    pool = bf16_tensor(case.pool)
+    rng = np.random.default_rng(11)
+    ids_h = rng.permutation(case.in_use_ids)[:n_list].astype(np.int32) if n_list else np.zeros(0, np.int32)
+    assert len(ids_h) == n_list
+    ids = torch.from_numpy(np.concatenate([ids_h, np.zeros(1, np.int32)])).cuda()[:n_list]   # never an empty allocation
+    staging = torch.full((2 * chunk,) + pool.shape[1:], float("nan"), dtype=torch.bfloat16, device="cuda")
+    host = torch.zeros((max(n_list, 1) + 1,) + pool.shape[1:], dtype=torch.bfloat16).pin_memory()
+    pack_s, copy_s = torch.cuda.Stream(), torch.cuda.Stream()
+    pack_s.wait_stream(torch.cuda.current_stream())
+    for rnd in range(2):                                                # twice: the halves and events are reused
+        host.zero_()
+        kvflow.kv_pack_blocks_staged(host, pool, ids, staging, chunk, pack_s, copy_s, n=n_list)
+        copy_s.synchronize()
+        pack_s.synchronize()
+        got = host_bits(host)
+        if n_list:
+            assert np.array_equal(got[:n_list], oracle.pack_blocks(case.pool, ids_h)), f"round {rnd}"
+        assert not got[n_list:].any(), "wrote past the end of the list"
+
+
+def test_staged_transfer_on_one_stream_and_bad_arguments(oracle):
+    g = W.Geometry(8, 2, 64, 16)
+    case = W.make_decode_case("t", 309, g, np.array([300, 77], np.int32), dirty="fraction", n_dirty=20)
+    pool = bf16_tensor(case.pool)
+    ids = torch.from_numpy(case.dirty_ids).cuda()
+    n = len(case.dirty_ids)
+    staging = torch.empty((2 * 3,) + pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+    host = torch.zeros((n,) + pool.shape[1:], dtype=torch.bfloat16).pin_memory()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    kvflow.kv_pack_blocks_staged(host, pool, ids, staging, 3, s, s)     # same stream: packs and copies alternate
+    s.synchronize()
+    assert np.array_equal(host_bits(host), oracle.pack_blocks(case.pool, case.dirty_ids))
+    with pytest.raises(ValueError):
+        kvflow.kv_pack_blocks_staged(host, pool, ids, staging[:5], 3, s, s)          # staging smaller than two halves
+    with pytest.raises(ValueError):
+        kvflow.kv_pack_blocks_staged(host[:n - 1], pool, ids, staging, 3, s, s)      # destination too small
+    with pytest.raises(kvflow.KvflowError) as e:
+        kvflow.kv_pack_blocks_staged(host, pool, ids, staging, 0, s, s)
+    assert e.value.status == -2

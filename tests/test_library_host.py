@@ -111,6 +111,18 @@ def test_block_bytes_workgroups_and_workspace_size(lib):
     assert kvflow.kv_decode_workspace_bytes(8, 33, 8, 128, 65536) == 0
 
 
+def test_staged_pack_rejects_bad_arguments_before_any_launch(lib):
+    from paper_2601_22438_amd import kvflow
+    ok = desc(kvflow)
+    sp = lambda dst=0x20000, p=ok, ids=0x30000, n=4, st=0x40000, chunk=2: lib.kv_pack_blocks_staged(
+        dst, ctypes.byref(p), ids, n, st, chunk, None, None)
+    assert sp(n=0) == 0
+    assert sp(dst=0) == -1 and sp(ids=0) == -1 and sp(st=0) == -1 and sp(p=desc(kvflow, base=0)) == -1
+    assert sp(n=-1) == -2 and sp(chunk=0) == -2 and sp(chunk=-5) == -2
+    assert sp(dst=0x20008) == -4 and sp(st=0x40004) == -4
+    assert sp(p=desc(kvflow, d=48)) == -3
+
+
 def test_status_strings(lib):
     from paper_2601_22438_amd import kvflow
     assert kvflow.kv_status_string(0) == "ok"
