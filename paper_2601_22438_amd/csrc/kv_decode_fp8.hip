@@ -3,11 +3,11 @@
 //
 // What changes is the front end.  A tile is 64 tokens, so that a wavefront still has 16 KiB of
 // loads in flight.  K rows are loaded as 16 consecutive channels per lane and converted in
-// registers (v_cvt_pk_f32_fp8, exact, then to bf16, exact) into two MFMA A operands; Q^T is
+// registers (v_cvt_scalef32_pk_bf16_fp8 with scale 1, exact) into two MFMA A operands; Q^T is
 // loaded with the matching channel order.  V rows are loaded fully coalesced, converted, and
 // staged in LDS as bf16, so the transposed read and the second product are those of the bf16
 // kernel.  The per-tensor scales never touch the data: the K scale is folded into the softmax
-// scale on the host, the V scale multiplies the output when a row is normalised.
+// scale on the host, the V scale multiplies the output in the merge kernel.
 // The tile is processed as two 32-token halves (QK^T for both, then per half: V staging,
 // softmax, PV); K registers are refilled after the four QK^T products, V registers after the
 // second half has been staged.
@@ -26,7 +26,11 @@ struct Shape8 {
     static constexpr int kVLanesPerRow = D / 16;     // lanes covering one V row with 16-byte loads
     static constexpr int kVRowsPerLoad = 64 / kVLanesPerRow;
     static constexpr int kVLoadsPerHalf = 32 / kVRowsPerLoad;
-    static constexpr int kPitch = D * 2 + 32;        // LDS row pitch of the bf16 staging tile
+    // LDS row pitch of the bf16 staging tile.  A lane stages 32 bytes (16 converted channels) with two
+    // 16-byte stores that leave 16-byte holes; at D 128 a pitch of 272 lets the next row's stores fall
+    // into them (a pitch of 288 made the stores of neighbouring rows collide: bank conflicts for as many
+    // cycles as the LDS was busy), and the transposed read is as fast with either.
+    static constexpr int kPitch = D == 128 ? D * 2 + 16 : D * 2 + 32;
     static constexpr int kVTileBytes = 32 * kPitch;
     static constexpr int kRecord = D + kRecordPad;
 };
@@ -37,21 +41,23 @@ struct TileDesc8 {
     int pb[4];
 };
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // 16 FP8 E4M3 values -> 8 + 8 bf16 values, element order kept (byte i of the load is element i).
+// v_cvt_scalef32_pk_bf16_fp8 turns two FP8 bytes (the low or the high half of a word) into a packed
+// bf16 pair in one instruction; with scale 1 the conversion is exact (every E4M3 number is a bf16 number).
 __device__ __forceinline__ void fp8x16_to_bf16(u32x4 raw, bf16x8& lo, bf16x8& hi)
 {
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-        const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], false);
-        const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], true);
+        const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[w], 1.0f, false);
+        const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[w], 1.0f, true);
         bf16x8& dst = w < 2 ? lo : hi;
         const int o = (w & 1) * 4;
-        dst[o + 0] = (__bf16)a.x;
-        dst[o + 1] = (__bf16)a.y;
-        dst[o + 2] = (__bf16)b.x;
-        dst[o + 3] = (__bf16)b.y;
+        dst[o + 0] = a.x;
+        dst[o + 1] = a.y;
+        dst[o + 2] = b.x;
+        dst[o + 3] = b.y;
     }
 }
 

@@ -198,18 +198,18 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             }
         }
     };
-    // 8 E4M3 bytes (two words) -> 8 bf16, element order kept
+    // 8 E4M3 bytes (two words) -> 8 bf16, element order kept (v_cvt_scalef32_pk_bf16_fp8 with scale 1: exact)
     auto widen = [](u32x4 raw) -> u32x4 {
-        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
         bf16x8 o;
 #pragma unroll
         for (int w = 0; w < 2; ++w) {
-            const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], false);
-            const f32x2 b2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], true);
-            o[4 * w + 0] = (__bf16)a.x;
-            o[4 * w + 1] = (__bf16)a.y;
-            o[4 * w + 2] = (__bf16)b2.x;
-            o[4 * w + 3] = (__bf16)b2.y;
+            const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[w], 1.0f, false);
+            const bf16x2 b2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[w], 1.0f, true);
+            o[4 * w + 0] = a.x;
+            o[4 * w + 1] = a.y;
+            o[4 * w + 2] = b2.x;
+            o[4 * w + 3] = b2.y;
         }
         return __builtin_bit_cast(u32x4, o);
     };

@@ -56,6 +56,25 @@ def test_fp8_single_token_returns_decoded_v_times_scale_exactly(oracle):
     assert np.array_equal(got, want)
 
 
+def test_fp8_every_code_through_the_kernels_conversion(oracle):
+    """Single-token contexts whose V rows enumerate all 256 E4M3 codes (every code in every byte position of
+    a 16-byte load): the kernel returns decoded code x v_scale exactly, NaN codes as NaN, in element order."""
+    g = W.Geometry(8, 2, 128, 16, kv_elt_bytes=1)
+    case = W.make_decode_case("codes", 509, g, np.array([1] * 16, np.int32), max_blocks_per_seq=2)
+    pool = case.pool.copy()
+    for b in range(case.batch):                               # sequence b: codes rotated by b, so each code meets each lane slot
+        blk = case.block_table[b, 0]
+        pool[blk, 1, :, 0, :] = ((np.arange(256) + 16 * b + b) % 256).astype(np.uint8).reshape(2, 128)
+        pool[blk, 0, :, 0, :] = 0x38                          # K = 1: finite scores
+    vs = 0.375
+    want = oracle.decode_attn(case.q, pool, case.block_table, case.context_lens, g.scale, k_scale=1.0, v_scale=vs)
+    got = DeviceCase(case, pool_bits=pool, k_scale=1.0, v_scale=vs).decode(torch.float32).to(torch.float64).cpu().numpy()
+    nan = np.isnan(want)
+    assert nan.sum() == case.batch * g.group * 2              # codes 0x7F and 0xFF, once per query head of their KV head
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+
+
 def test_fp8_zero_length_poison_and_permutation(oracle):
     case = make(507, 32, 8, 128, 16, [0, 37, 130, 5, 0, 64], MB=12)
     g = case.geom

@@ -69,6 +69,42 @@ def test_pack_restore_empty_list_and_prefix(oracle):
     assert np.array_equal(got[:4], case.pool[case.dirty_ids[:4]]) and not got[4:].any()
 
 
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 63, 1000])
+def test_pack_restore_list_lengths_around_the_xcd_split(oracle, n):
+    """The list is dealt to the eight XCDs in contiguous parts: lengths below, at and above eight entries."""
+    case = make(107, 8, 2, 64, 16, [16 * 1000], NB=1200, dirty="any", n_dirty=1000)
+    pool = bf16_tensor(case.pool)
+    ids_h = case.dirty_ids[:n].copy()
+    ids = torch.from_numpy(ids_h).cuda()
+    replica = torch.zeros((n + 1,) + pool.shape[1:], dtype=torch.bfloat16, device="cuda")
+    kvflow.kv_pack_blocks(replica, pool, ids)
+    torch.cuda.synchronize()
+    got = bits_of(replica)
+    assert np.array_equal(got[:n], oracle.pack_blocks(case.pool, ids_h)) and not got[n:].any()
+    target = torch.zeros_like(pool)
+    kvflow.kv_restore_blocks(target, replica, ids)
+    torch.cuda.synchronize()
+    want = np.zeros_like(case.pool)
+    oracle.restore_blocks(want, got[:n], ids_h)
+    assert np.array_equal(bits_of(target), want)
+
+
+def test_pack_list_longer_than_one_launch(oracle):
+    """More list entries than one launch covers (2^21 workgroups): the second launch continues the list and
+    the replica where the first one stopped.  Blocks of 2 KiB (FP8, one KV head, head_dim 64), ids with repeats."""
+    g = W.Geometry(1, 1, 64, 16, kv_elt_bytes=1)
+    case = W.make_decode_case("t", 109, g, np.array([16 * 500], np.int32), num_blocks=512, dirty="any", n_dirty=8)
+    assert g.block_bytes == 2048
+    n = (1 << 21) + 1000
+    ids_h = np.random.default_rng(5).integers(0, case.num_blocks, size=n, dtype=np.int32)
+    pool = kvflow.Fp8Pool(torch.from_numpy(case.pool).cuda(), 1.0, 1.0)
+    replica = torch.zeros((n + 1,) + case.pool.shape[1:], dtype=torch.uint8, device="cuda")
+    kvflow.kv_pack_blocks(replica, pool, torch.from_numpy(ids_h).cuda())
+    torch.cuda.synchronize()
+    got = replica.cpu().numpy()
+    assert np.array_equal(got[:n], oracle.pack_blocks(case.pool, ids_h)) and not got[n:].any()
+
+
 def test_tiny_config_pack_restore_round_trip(oracle):
     case = W.tiny()
     pool = bf16_tensor(case.pool)
