@@ -2,19 +2,24 @@
  * kvflow.h - C ABI of the paged KV-cache data path for one MI355X (gfx950).
  *
  * The library serves the two uses the paper makes of a block-paged KV cache
- * (Sec. 3.2 item 3, "Background KV Cache Replication"; overhead in Sec. 4.4):
+ * (Sec. 3.2 item 3, background replication of the KV cache; overhead in Sec. 4.4):
  *   1. the decode step itself: one query token per in-flight request attends to
  *      that request's cached keys/values, stored as fixed-size blocks that a
  *      per-request block table maps from logical to physical position;
  *   2. block-by-block replication: the blocks a step has written are gathered
  *      into a contiguous replica buffer on a separate stream (pack), and a
  *      replication target scatters a replica into its own pool so that requests
- *      continue from the replicated state (restore).
+ *      go on from the replica (restore).
+ * The method's contract is three calls: kv_decode_attn, kv_pack_blocks, kv_restore_blocks.  The
+ * calls that widen it (append, dirty list, counted and staged pack, token gather, recomputation)
+ * say so where they are declared.  kv_probe_stream, kv_decode_workgroups and kv_validate_* are
+ * diagnostics for benchmarks and debugging, outside the method's contract.
  *
  * General rules
  *   - Every pointer is a DEVICE pointer unless its comment says "host".
- *   - The caller owns every buffer.  The library allocates no memory, keeps no
- *     state between calls and never synchronises: a call validates its host
+ *   - The caller owns every buffer.  The library allocates no device memory, keeps no
+ *     state between calls (but the address of kv_decode_attn_static's fixed array, looked
+ *     up once per GPU) and never synchronises: a call validates its host
  *     arguments, enqueues kernels on `stream` (a hipStream_t passed as void*,
  *     NULL = the default stream) and returns.  Buffers must stay alive and
  *     unmodified until the stream has passed the enqueued work.
