@@ -135,8 +135,7 @@ __device__ __forceinline__ void leave_row(float* __restrict__ ws_records, const 
 // issued before the first use: the threads are kSlices groups of D/4 lanes, a lane owns 4
 // channels, group s takes runs s, s + kSlices, ... of the pass, and the running max and
 // denominators of the pass go through LDS.  Partial sums of the groups are added in group order.
-// Two sizes: 256 threads when there are few (sequence, head) pairs with many records each, 64
-// when there are thousands of pairs with a handful of records (more workgroups resident at once).
+// For batches with thousands of pairs and a handful of records each, see decode_merge_rows_kernel.
 constexpr int kMergePer = 8;                         // records per thread and pass
 
 template <int D, int kMergeThreads>
@@ -217,13 +216,85 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const Decod
     }
 }
 
+// The same merge for batches with thousands of (sequence, head) pairs and a handful of records per
+// pair: one 256-lane workgroup per (sequence, KV head) row takes all query heads of the row, a lane
+// owns 4 channels of one head and walks that head's records in run order (all loads of up to
+// kMergePer records in flight).  An eighth of the workgroups of the per-pair kernel, which at these
+// shapes is bound by their dispatch.
+template <int D>
+__global__ __launch_bounds__(256) void decode_merge_rows_kernel(const DecodeParams p, int W)
+{
+    constexpr int kRecord = D + kRecordPad;
+    constexpr int kLanes = D / 4;
+    constexpr int kHeads = 256 / kLanes;                              // query heads per pass
+    const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int Hkv = p.num_kv_heads, G = p.group;
+    const int n = p.ws_cum[b + 1] - p.ws_cum[b];
+    const int c = tid % kLanes;
+    int w0 = 0, nr = 0;
+    if (n > 0) {
+        const int T = Hkv * p.ws_cum[p.batch];
+        const int base = T / W, rem = T % W;
+        const int first = Hkv * p.ws_cum[b] + kvh * n;                // flat range of this row
+        w0 = run_of_tile(first, base, rem);
+        nr = run_of_tile(first + n - 1, base, rem) - w0 + 1;
+    }
+    for (int hg = tid / kLanes; hg < G; hg += kHeads) {
+        const int64_t out0 = ((int64_t)b * p.num_q_heads + (int64_t)kvh * G + hg) * D + 4 * c;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};                               // empty sequence: a row of zeros
+        if (n > 0) {
+            const int64_t rec_stride = (int64_t)G * kRecord;          // run w -> run w + 1, same row and head
+            const float* recs = p.ws_records + ((w0 + (int64_t)b * Hkv + kvh) * G + hg) * kRecord;
+            float M = -INFINITY, lsum = 0.f;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int r0 = 0; r0 < nr; r0 += kMergePer) {
+                f32x4 v[kMergePer];
+                float m[kMergePer], l[kMergePer];
+#pragma unroll
+                for (int k = 0; k < kMergePer; ++k) {
+                    const int r = min(r0 + k, nr - 1);               // past the end: the last record again, not used
+                    v[k] = *(const f32x4*)(recs + r * rec_stride + 4 * c);
+                    m[k] = recs[r * rec_stride + D];
+                    l[k] = recs[r * rec_stride + D + 1];
+                }
+                float Mn = M;
+#pragma unroll
+                for (int k = 0; k < kMergePer; ++k) if (r0 + k < nr) Mn = fmaxf(Mn, m[k]);
+                const float a = fast_exp2(M - Mn);                    // 0 on the first pass (M = -inf, Mn finite)
+                M = Mn;
+                acc *= a;
+                lsum *= a;
+#pragma unroll
+                for (int k = 0; k < kMergePer; ++k) {
+                    if (r0 + k < nr) {
+                        const float wgt = fast_exp2(m[k] - Mn);
+                        acc += wgt * v[k];
+                        lsum += wgt * l[k];
+                    }
+                }
+            }
+            o = acc / lsum * p.out_scale;
+        }
+        if (p.out_f32) {
+            *(f32x4*)((float*)p.out + out0) = o;
+        } else {
+            typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+            bf16x4 h;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) h[i] = (__bf16)o[i];
+            *(bf16x4*)((__bf16*)p.out + out0) = h;
+        }
+    }
+}
+
 // Launches the merge kernel that fits the number of (sequence, head) pairs.
 template <int D>
 static hipError_t launch_merge(const DecodeParams& p, int workgroups, hipStream_t stream)
 {
     const dim3 mgrid((uint32_t)p.num_q_heads, (uint32_t)p.batch, 1);
     if ((int64_t)p.batch * p.num_q_heads >= 2048)
-        hipLaunchKernelGGL((decode_merge_kernel<D, 64>), mgrid, dim3(64), 0, stream, p, workgroups * kDecodeWaves);
+        hipLaunchKernelGGL(decode_merge_rows_kernel<D>, dim3((uint32_t)p.num_kv_heads, (uint32_t)p.batch, 1), dim3(256), 0,
+                           stream, p, workgroups * kDecodeWaves);
     else
         hipLaunchKernelGGL((decode_merge_kernel<D, 256>), mgrid, dim3(256), 0, stream, p, workgroups * kDecodeWaves);
     return hipGetLastError();
