@@ -30,8 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core peak
 # HBM traffic per decode launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
 # WRITE_SIZE), scaled by the same counters on a plain copy of known size; see profiles/.  Valid
 # only for the kernel sources (kv_decode.hip + kv_decode_common.h) the counters were taken with.
-DECODE_TRAFFIC = {"kernel_sha256": "37960c7caa488a8c328e50845a5e15578eaaae9a379a129e61431bef8a43788e",
-                  "fetch_bytes": 1290268096, "write_bytes": 2371546}
+DECODE_TRAFFIC = {"kernel_sha256": "3472378714227b721abb12222d69300c8cdb5d05e02425179b5562a100ae2f66",
+                  "fetch_bytes": 1290203005, "write_bytes": 2371422}
 
 PAPER_CONTEXT = {
     "note": "end-to-end serving figures from the paper, other hardware, context only",

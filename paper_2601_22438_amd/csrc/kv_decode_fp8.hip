@@ -27,9 +27,12 @@ struct Shape8 {
     static constexpr int kVRowsPerLoad = 64 / kVLanesPerRow;
     static constexpr int kVLoadsPerHalf = 32 / kVRowsPerLoad;
     // LDS row pitch of the bf16 staging tile.  A lane stages 32 bytes (16 converted channels) with two
-    // 16-byte stores that leave 16-byte holes; at D 128 a pitch of 272 lets the next row's stores fall
-    // into them (a pitch of 288 made the stores of neighbouring rows collide: bank conflicts for as many
-    // cycles as the LDS was busy), and the transposed read is as fast with either.
+    // 16-byte stores.  Measured on the LDS alone, 16-byte stores run at about 64 bytes per clock whatever
+    // the pitch (the bank-conflict counter charges them the extra cycles), and the transposed 8-byte reads
+    // run conflict-free at pitches of 272, 288 and 320 but at a third of that rate at 256 and half at 264.
+    // Making a row's first stores contiguous (channels permuted within the row, reads following) took 15 %
+    // off the LDS time in isolation and nothing measurable off the kernel: the LDS is busy for under a
+    // tenth of a wave's cycles here.
     static constexpr int kPitch = D == 128 ? D * 2 + 16 : D * 2 + 32;
     static constexpr int kVTileBytes = 32 * kPitch;
     static constexpr int kRecord = D + kRecordPad;
