@@ -557,7 +557,39 @@ def bench_yardsticks(args, kvflow, W):
         d = time_calls(fn, 10, 3)
         gbps = traffic / (d["mean_ms"] * 1e-3) / 1e9
         out[name] = {**d, "traffic_GBps": gbps, "frac_hbm_peak": gbps / HBM_PEAK_GBPS}
+    del a, b, a32, b32
+    torch.cuda.empty_cache()
+    out["matrix_core"] = bench_matrix_yardsticks(kvflow)
     return out
+
+
+def bench_matrix_yardsticks(kvflow):
+    """What bounds the recomputation kernel: the MFMA rate on registers alone with zero and with random operands
+    (the device lowers its clock under random data), the vector work of a softmax step, and how much of it
+    hides under the matrix work of the wavefront that shares the SIMD."""
+    import torch
+    sink = torch.empty(kvflow.KV_PROBE_MATRIX_SINK_BYTES // 4, dtype=torch.float32, device="cuda")
+    iters = 20000
+    waves, mfma_per_block = 256 * 8, 32
+    res = {"iterations": iters,
+           "blocks": "matrix block = 32 MFMA 16x16x32 bf16 on registers; vector block = 80 fma + 16 exp2; "
+                     "256 workgroups of 8 wavefronts, wavefronts w and w + 4 share a SIMD"}
+    cyc = lambda ms: ms * 1e-3 * 2.4e9 / iters           # cycles per iteration at the nominal 2.4 GHz
+    for mode, name, active_waves in ((0, "matrix_only_zero_operands", waves), (1, "matrix_only_random_operands", waves),
+                                     (4, "matrix_on_half_the_wavefronts_partners_idle", waves // 2)):
+        d = time_calls(lambda: kvflow.kv_probe_matrix(mode, iters, sink), 5, 2)
+        tflops = active_waves * iters * mfma_per_block * 16384 / (d["mean_ms"] * 1e-3) / 1e12
+        res[name] = {"mean_ms": d["mean_ms"], "TFLOPps": tflops, "frac_mfma_peak": tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "cycles_per_iteration_at_2p4GHz": cyc(d["mean_ms"])}
+    for mode, name in ((2, "vector_only_all_wavefronts"), (5, "vector_on_half_the_wavefronts_partners_idle"),
+                       (3, "matrix_wavefronts_beside_vector_partners")):
+        d = time_calls(lambda: kvflow.kv_probe_matrix(mode, iters, sink), 5, 2)
+        res[name] = {"mean_ms": d["mean_ms"], "cycles_per_iteration_at_2p4GHz": cyc(d["mean_ms"])}
+    m, v = (res["matrix_on_half_the_wavefronts_partners_idle"]["cycles_per_iteration_at_2p4GHz"],
+            res["vector_on_half_the_wavefronts_partners_idle"]["cycles_per_iteration_at_2p4GHz"])
+    both = res["matrix_wavefronts_beside_vector_partners"]["cycles_per_iteration_at_2p4GHz"]
+    res["vector_work_hidden_under_matrix_work_frac"] = (m + v - both) / min(m, v)
+    return res
 
 
 def main():

@@ -12,7 +12,7 @@
  *      go on from the replica (restore).
  * The method's contract is three calls: kv_decode_attn, kv_pack_blocks, kv_restore_blocks.  The
  * calls that widen it (append, dirty list, counted and staged pack, token gather, recomputation)
- * say so where they are declared.  kv_probe_stream, kv_decode_workgroups and kv_validate_* are
+ * say so where they are declared.  kv_probe_stream, kv_probe_matrix, kv_decode_workgroups and kv_validate_* are
  * diagnostics for benchmarks and debugging, outside the method's contract.
  *
  * General rules
@@ -356,6 +356,26 @@ int kv_validate_prefill(const kv_pool_desc* pool, const int32_t* block_table, in
  * a, b: device pointers, 16-byte aligned, must not overlap.  Errors: SHAPE, NULL, ALIGN, LAUNCH.
  */
 int kv_probe_stream(int32_t mode, void* a, const void* b, size_t bytes, void* stream);
+
+/*
+ * Matrix-core yardstick for the recomputation kernel's roofline (for callers that measure): 256
+ * workgroups of 8 wavefronts (one per compute unit; wavefronts w and w + 4 share a SIMD) repeat,
+ * `iters` times, a matrix block (32 MFMAs 16x16x32 bf16 on registers: 8 A fragments, 4 B fragments,
+ * 16 accumulators; 32 * 16384 flop per wavefront) and/or a vector block (80 fused multiply-adds and
+ * 16 exp2 on 16 values: about the vector work of one 32-key x 32-query softmax step).
+ *   mode 0  all wavefronts: matrix blocks, operands all zero
+ *   mode 1  all wavefronts: matrix blocks, operands uniform in [-1, 1) (the device lowers its clock
+ *           under the switching activity of such data; compare with mode 0)
+ *   mode 2  all wavefronts: vector blocks
+ *   mode 3  wavefronts 0-3 matrix blocks (operands as in mode 1), their SIMD partners vector blocks
+ *   mode 4  wavefronts 0-3 matrix blocks, the partners idle
+ *   mode 5  wavefronts 4-7 vector blocks, the partners idle
+ * sink: device pointer, 16-byte aligned, at least KV_PROBE_MATRIX_SINK_BYTES bytes, overwritten
+ * with values of no meaning.  Errors: SHAPE (mode, negative iters), NULL, ALIGN, WORKSPACE (sink
+ * too small), LAUNCH.
+ */
+#define KV_PROBE_MATRIX_SINK_BYTES (256u * 512u * 4u)
+int kv_probe_matrix(int32_t mode, int32_t iters, void* sink, size_t sink_bytes, void* stream);
 
 /* Static, human-readable text for a kv_status value. */
 const char* kv_status_string(int status);

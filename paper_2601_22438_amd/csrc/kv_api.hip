@@ -107,6 +107,11 @@ int copy_blocks(void* replica, const kv_pool_desc* pool, const int32_t* block_id
 
 }  // namespace
 
+namespace kvflow {
+// defined beside the other yardstick kernels
+hipError_t launch_probe_matrix(int mode, int iters, float* sink, hipStream_t stream);
+}  // namespace kvflow
+
 extern "C" {
 
 size_t kv_block_bytes(const kv_pool_desc* pool)
@@ -499,6 +504,15 @@ int kv_probe_stream(int32_t mode, void* a, const void* b, size_t bytes, void* st
     if (!aligned16(a) || (kind != 1 && !aligned16(b))) return KV_ERR_ALIGN;
     if (mode <= 2 && bytes > ((size_t)32 << 30)) return KV_ERR_SHAPE;
     return launch_probe(mode, a, b, bytes, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
+}
+
+int kv_probe_matrix(int32_t mode, int32_t iters, void* sink, size_t sink_bytes, void* stream)
+{
+    if (mode < 0 || mode > 5 || iters < 0) return KV_ERR_SHAPE;
+    if (!sink) return KV_ERR_NULL;
+    if (!aligned16(sink)) return KV_ERR_ALIGN;
+    if (sink_bytes < KV_PROBE_MATRIX_SINK_BYTES) return KV_ERR_WORKSPACE;
+    return launch_probe_matrix(mode, iters, (float*)sink, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_ERR_LAUNCH;
 }
 
 const char* kv_status_string(int status)

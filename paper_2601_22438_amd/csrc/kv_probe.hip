@@ -5,6 +5,10 @@
 // the XCDs in contiguous eighths, one 16 KiB workgroup per piece, stores written through at device
 // scope (the design of the block-copy kernels); modes 3-5 walk the buffer in workgroup order with
 // plain non-temporal accesses (a persistent grid for the read).
+// A third yardstick, for the recomputation kernel's roofline: what the matrix cores reach on registers
+// alone (which depends on the operand data: the device lowers its clock under the switching activity
+// of random operands), what the vector work of a softmax step costs, and how much of the one hides
+// under the other when the two run on the wavefronts that share a SIMD.
 
 #include "kv_internal.h"
 
@@ -120,6 +124,81 @@ hipError_t launch_probe(int mode, void* a, const void* b, size_t bytes, hipStrea
         hipLaunchKernelGGL(probe_write_kernel, dim3((uint32_t)groups), block, 0, stream, (u32x4*)a, n);
     else
         hipLaunchKernelGGL(probe_copy_kernel, dim3((uint32_t)groups), block, 0, stream, (u32x4*)a, (const u32x4*)b, n);
+    return hipGetLastError();
+}
+
+// ---- matrix-core / vector-ALU yardstick.  One workgroup of 8 wavefronts per compute unit; wavefronts
+//      w and w + 4 share a SIMD.  A matrix block is 32 v_mfma_f32_16x16x32_bf16 over 8 distinct A
+//      fragments, 4 distinct B fragments and 16 accumulators (no instruction waits for another); a
+//      vector block is 80 fused multiply-adds and 16 exp2 on 16 values (the vector work of one
+//      32-key x 32-query softmax step is about that).
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 probe_bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float probe_f32x4;
+constexpr int kMatrixThreads = 512;
+constexpr int kMatrixGroups = 256;
+
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+
+template <bool RANDOM, bool MATRIX_FIRST, bool MATRIX_LAST, bool VECTOR_FIRST, bool VECTOR_LAST>
+__global__ __launch_bounds__(kMatrixThreads) void probe_matrix_kernel(float* __restrict__ sink, int iters, float fa, float fb)
+{
+    const bool last = threadIdx.x >= kMatrixThreads / 2;              // wave-uniform: the SIMD partners
+    const bool do_matrix = last ? MATRIX_LAST : MATRIX_FIRST;
+    const bool do_vector = last ? VECTOR_LAST : VECTOR_FIRST;
+    float result = 0.f;
+    if (do_matrix) {
+        probe_bf16x8 a[8], b[4];
+        for (int r = 0; r < 12; ++r) {
+            probe_bf16x8 v;
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t h = probe_hash((blockIdx.x * (uint32_t)kMatrixThreads + threadIdx.x) * 131u + r * 17u + i);
+                v[i] = (__bf16)(RANDOM ? (float)(h >> 8) * (1.0f / 8388608.0f) - 1.0f : 0.f);   // uniform in [-1, 1)
+            }
+            if (r < 8) a[r] = v; else b[r - 8] = v;
+        }
+        probe_f32x4 acc[16];
+        for (int c = 0; c < 16; ++c) acc[c] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int c = 0; c < 32; ++c)
+                acc[c % 16] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c % 8], b[c % 4], acc[c % 16], 0, 0, 0);
+            if ((it & 1023) == 1023)                                  // keep the sums finite
+                for (int c = 0; c < 16; ++c) acc[c] *= 1e-3f;
+        }
+        for (int c = 0; c < 16; ++c) result += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
+    }
+    if (do_vector) {
+        float x[16];
+        for (int i = 0; i < 16; ++i) x[i] = -(float)((threadIdx.x + i) & 7);
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 80; ++r) x[r % 16] = __builtin_fmaf(x[r % 16], fa, fb);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) x[e] = __builtin_amdgcn_exp2f(x[e]) - 1.5f;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (int i = 0; i < 16; ++i) result += x[i];
+    }
+    sink[blockIdx.x * kMatrixThreads + threadIdx.x] = result;
+}
+
+hipError_t launch_probe_matrix(int mode, int iters, float* sink, hipStream_t stream)
+{
+    const dim3 grid(kMatrixGroups), block(kMatrixThreads);
+    const float fa = 0.999f, fb = -0.001f;
+    switch (mode) {
+        case 0: hipLaunchKernelGGL((probe_matrix_kernel<false, true, true, false, false>), grid, block, 0, stream, sink, iters, fa, fb); break;
+        case 1: hipLaunchKernelGGL((probe_matrix_kernel<true, true, true, false, false>), grid, block, 0, stream, sink, iters, fa, fb); break;
+        case 2: hipLaunchKernelGGL((probe_matrix_kernel<true, false, false, true, true>), grid, block, 0, stream, sink, iters, fa, fb); break;
+        case 3: hipLaunchKernelGGL((probe_matrix_kernel<true, true, false, false, true>), grid, block, 0, stream, sink, iters, fa, fb); break;
+        case 4: hipLaunchKernelGGL((probe_matrix_kernel<true, true, false, false, false>), grid, block, 0, stream, sink, iters, fa, fb); break;
+        case 5: hipLaunchKernelGGL((probe_matrix_kernel<true, false, false, false, true>), grid, block, 0, stream, sink, iters, fa, fb); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

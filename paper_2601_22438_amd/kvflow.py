@@ -86,6 +86,8 @@ def load() -> ctypes.CDLL:
     lib.kv_validate_block_ids.argtypes = [PD, P, I64, I32, P]
     lib.kv_probe_stream.restype = ctypes.c_int
     lib.kv_probe_stream.argtypes = [I32, P, P, SZ, P]
+    lib.kv_probe_matrix.restype = ctypes.c_int
+    lib.kv_probe_matrix.argtypes = [I32, I32, P, SZ, P]
     lib.kv_status_string.restype, lib.kv_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
     _lib = lib
     return lib
@@ -361,6 +363,17 @@ def kv_collect_dirty(dirty_bitmap, num_blocks, dirty_ids, dirty_count, clear=Tru
 def kv_probe_stream(mode, a, b, nbytes, stream=None) -> None:
     """Enqueue one plain streaming kernel: mode 0 reads b, 1 writes a, 2 copies b to a (nbytes, multiple of 16)."""
     _check(load().kv_probe_stream(int(mode), _ptr(a), _ptr(b), int(nbytes), _stream_handle(stream)))
+
+
+KV_PROBE_MATRIX_SINK_BYTES = 256 * 512 * 4
+
+
+def kv_probe_matrix(mode, iters, sink, stream=None) -> None:
+    """Enqueue the matrix-core / vector-ALU yardstick kernel (modes 0-5, see the header); sink: device tensor of
+    at least KV_PROBE_MATRIX_SINK_BYTES bytes."""
+    _dev(sink, "sink")
+    _check(load().kv_probe_matrix(int(mode), int(iters), _ptr(sink), sink.numel() * sink.element_size(),
+                                  _stream_handle(stream)))
 
 
 def kv_validate_decode(pool, block_table, context_lens, max_context_len, stream=None) -> int:

@@ -352,3 +352,20 @@ def test_streaming_probes_copy_exactly_and_leave_the_sink_alone(design):
         kvflow.kv_probe_stream(design + 2, small, src, m)
         torch.cuda.synchronize()
         assert torch.equal(small[:m], src[:m]) and torch.all(small[m:] == 0)
+
+
+def test_matrix_probe_runs_every_mode_and_leaves_zeros_for_zero_operands():
+    """The matrix-core yardstick: every mode returns, writes only its sink, and with all-zero operands (mode 0)
+    every accumulator, hence every sink entry, is zero."""
+    n = kvflow.KV_PROBE_MATRIX_SINK_BYTES // 4
+    buf = torch.full((n + 64,), 7.0, dtype=torch.float32, device="cuda")
+    for mode in range(6):
+        kvflow.kv_probe_matrix(mode, 50, buf[:n])
+        torch.cuda.synchronize()
+        assert torch.isfinite(buf).all(), f"mode {mode}"
+        assert (buf[n:] == 7.0).all(), f"mode {mode}: wrote past the sink"
+        if mode == 0:
+            assert (buf[:n] == 0).all()
+    with pytest.raises(kvflow.KvflowError):
+        kvflow.kv_probe_matrix(1, 10, buf[: n - 4])
+

@@ -228,6 +228,13 @@ def test_probe_rejects_bad_arguments_before_any_launch(lib):
     assert pr(a=0x20008) == -4 and pr(b=0x30004) == -4
 
 
+def test_matrix_probe_rejects_bad_arguments_before_any_launch(lib):
+    need = 256 * 512 * 4
+    pm = lambda mode=1, iters=10, sink=0x20000, n=need: lib.kv_probe_matrix(mode, iters, sink, n, None)
+    assert pm(mode=6) == -2 and pm(mode=-1) == -2 and pm(iters=-1) == -2
+    assert pm(sink=0) == -1 and pm(sink=0x20008) == -4 and pm(n=need - 4) == -5
+
+
 def test_binding_rejects_host_tensors_before_touching_the_library():
     """The binding's own checks run on the host: a tensor that is not GPU memory never reaches a kernel."""
     import torch
