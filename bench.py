@@ -291,6 +291,10 @@ def bench_replication_mix(args, kvflow, W):
     p = time_calls(lambda: kvflow.kv_pack_blocks(replica, pool, ids), 20, 5)
     side = torch.cuda.Stream()
     main = torch.cuda.current_stream()
+    # token-granular replication ships the new K/V rows only: their gather is the whole device-side cost
+    positions = torch.from_numpy(np.maximum(case.context_lens - 1, 0).astype(np.int32)).cuda()  # the newest slot
+    k_out = torch.empty((case.batch, g.num_kv_heads, g.head_dim), dtype=torch.bfloat16, device="cuda")
+    v_out = torch.empty_like(k_out)
 
     def train(n_iter, with_pack):
         """n_iter decode steps back to back on the main stream.  with_pack = "side": every step also
@@ -309,6 +313,8 @@ def bench_replication_mix(args, kvflow, W):
             dec.run()
             if with_pack == "same":
                 kvflow.kv_pack_blocks(replica, pool, ids)
+            if with_pack == "tokens":
+                kvflow.kv_gather_tokens(k_out, v_out, pool, dec.table, positions)
         if with_pack in ("side", "fork_only"):
             done = torch.cuda.Event()
             done.record(side)
@@ -322,8 +328,10 @@ def bench_replication_mix(args, kvflow, W):
     both_ms = min(train(30, "side") for _ in range(3))
     same_ms = min(train(30, "same") for _ in range(3))
     fork_ms = min(train(30, "fork_only") for _ in range(3))
+    tok_ms = min(train(30, "tokens") for _ in range(3))
     o = {"ms_per_step_decode_only": alone_ms, "ms_per_step_with_pack_on_side_stream": both_ms,
          "ms_per_step_with_pack_on_same_stream": same_ms,
+         "ms_per_step_with_token_rows_gathered_on_same_stream": tok_ms,
          "ms_per_step_with_the_fork_event_but_no_pack": fork_ms,
          "note": "eager launches; the side-stream figure includes one event record/wait per step between the two "
                  "streams, whose cost alone is the fork-event figure (it is paid once per fork, here once per "
@@ -376,14 +384,12 @@ def bench_replication_mix(args, kvflow, W):
     rs = np.random.SeedSequence(4242).spawn(2)
     k_new = bf16_dev(W.normal_bf16(rs[0], (case.batch, g.num_kv_heads, g.head_dim)))
     v_new = bf16_dev(W.normal_bf16(rs[1], (case.batch, g.num_kv_heads, g.head_dim)))
-    positions = torch.from_numpy(np.maximum(case.context_lens - 1, 0).astype(np.int32)).cuda()  # rewrite the newest slot
     bitmap = torch.zeros((case.num_blocks + 31) // 32, dtype=torch.int32, device="cuda")
     ids_dev = torch.empty(case.batch, dtype=torch.int32, device="cuda")
     cnt_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
     a_t = time_calls(lambda: kvflow.kv_append_tokens(pool, k_new, v_new, dec.table, positions, bitmap), 20, 5)
     c_t = time_calls(lambda: kvflow.kv_collect_dirty(bitmap, case.num_blocks, ids_dev, cnt_dev, False), 20, 5)
     p_t = time_calls(lambda: kvflow.kv_pack_blocks_counted(replica, pool, ids_dev, cnt_dev), 20, 5)
-    k_out, v_out = torch.empty_like(k_new), torch.empty_like(v_new)
     g_t = time_calls(lambda: kvflow.kv_gather_tokens(k_out, v_out, pool, dec.table, positions), 20, 5)
     loop = {"gather_tokens_us": g_t["mean_ms"] * 1e3,
             "bytes_per_step_block_granular": n * g.block_bytes,
@@ -463,6 +469,7 @@ def bench_replication_mix(args, kvflow, W):
         "decode_slowdown_pct": 100.0 * (both_ms / alone_ms - 1.0),
         "same_stream_slowdown_pct": 100.0 * (same_ms / alone_ms - 1.0),
         "fork_event_alone_slowdown_pct": 100.0 * (fork_ms / alone_ms - 1.0),
+        "token_rows_same_stream_slowdown_pct": 100.0 * (tok_ms / alone_ms - 1.0),
         "added_traffic_floor_pct": 100.0 * 2 * n * g.block_bytes / case.kv_bytes,
     }
 
